@@ -1,0 +1,172 @@
+/*
+ * libdgsp - CSR sparse x dense multiplication for AMD MI355X (gfx950), fp32.
+ *
+ * C-ABI of the hot path of "Efficient Sparse Matrix Kernels based on Adaptive
+ * Workload-Balancing and Parallel-Reduction" (arXiv 2106.16064):
+ *
+ *     Y[M x N] = A[M x K] * X[K x N]        (Section 1; N = 1 is SpMV)
+ *
+ * with A in CSR and X, Y dense.  Four kernels span the paper's design space
+ * (Section 2.1): {row-split, nnz-balanced} x {sequential, parallel reduction};
+ * a rule-based selector (Section 2.2) picks one from N and two row-length
+ * statistics.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers ordinary host memory.  The caller owns every buffer; the
+ *     library allocates nothing on the device and keeps no state between
+ *     calls apart from the selector thresholds (dgsp_set_thresholds).
+ *   - Indices are int32, zero based.  Values are fp32, accumulation is fp32
+ *     (the paper's float2/float4 loads, Section 2.1.2, imply single
+ *     precision).  The summation order differs between kernels, so results
+ *     agree with an exact sum to within c*eps32*(|A||X|) elementwise, not bit
+ *     for bit; the nnz-balanced kernels combine partial rows with fp32 atomic
+ *     adds and are not run-to-run bit-reproducible.
+ *   - X and Y are row-major with leading dimension N (the layout Section 2.1.2
+ *     needs: X[k,0], X[k,1] adjacent).
+ *   - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and the call returns.
+ *   - Return value: a dgsp_status_t.  On any error nothing has been enqueued.
+ */
+#ifndef DGSP_H
+#define DGSP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The four design points of Section 2.1 (Figure 1 of the paper). */
+typedef enum {
+    DGSP_RS_SR = 0, /* row-split, sequential reduction; sparse rows staged in LDS
+                       (coalesced sparse-row caching, Section 2.1.3)            */
+    DGSP_RS_PR = 1, /* row-split, parallel reduction (CSR-Vector lineage) with
+                       vector-type dense-row loads (Section 2.1.2)              */
+    DGSP_NB_SR = 2, /* nnz-balanced, sequential reduction, LDS-staged tiles      */
+    DGSP_NB_PR = 3, /* nnz-balanced, parallel reduction: wave64 vectorized
+                       segment reduction (Section 2.1.1)                        */
+    DGSP_AUTO = -1  /* let the library choose (see each entry point)            */
+} dgsp_algo_t;
+
+typedef enum {
+    DGSP_OK = 0,
+    DGSP_ERR_INVALID_ARG = 1, /* negative extent, NULL pointer with non-zero extent,
+                                 unknown algo, extent beyond the int32 index range   */
+    DGSP_ERR_UNSUPPORTED = 2, /* reserved                                            */
+    DGSP_ERR_LAUNCH = 3       /* the HIP runtime refused a launch                    */
+} dgsp_status_t;
+
+/* Row-length statistics of a CSR matrix, the selector's input (Section 2.2:
+ * avg_row and stdv_row; cv_row = stdv_row / avg_row is the paper's combined
+ * metric).  stdv_row is the population standard deviation over all M rows,
+ * empty rows included. */
+typedef struct {
+    int64_t M, K, nnz;
+    double avg_row, stdv_row, cv_row;
+    int64_t max_row, min_row;
+} dgsp_features_t;
+
+/* Selector thresholds (Section 2.2 says they are set empirically and prints no
+ * values; the defaults were fitted on MI355X).
+ *   N <= n_parallel_max          -> parallel reduction, else sequential
+ *   parallel:  avg_row >= pr_avg_row_min AND cv_row <= pr_cv_max -> row-split,
+ *              else nnz-balanced (the cv guard is an addition: the paper's
+ *              parallel-side rule looks at avg_row only; set pr_cv_max to a
+ *              huge value to get the paper's rule verbatim)
+ *   sequential: cv_row > sr_cv_min -> nnz-balanced, else row-split            */
+typedef struct {
+    int64_t n_parallel_max;
+    double pr_avg_row_min;
+    double pr_cv_max;
+    double sr_cv_min;
+} dgsp_thresholds_t;
+
+/*
+ * Y = A X (Section 1), one of the four kernels of Section 2.1.
+ *
+ *   M, K, N   extents, all >= 0; M + 1 and nnz must fit int32.
+ *   rowptr    device, int32[M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz.
+ *   colidx    device, int32[nnz], 0 <= colidx[p] < K; any order inside a row,
+ *             repeated (row, col) pairs add.  Out-of-range indices are
+ *             undefined behaviour (not checked on the device).
+ *   vals      device, fp32[nnz].
+ *   X         device, fp32[K*N], row-major, ld = N.  Read only.
+ *   Y         device, fp32[M*N], row-major, ld = N.  Overwritten (alpha = 1,
+ *             beta = 0); rows of A without entries give exact zeros.  Must not
+ *             overlap X.
+ *   algo      a dgsp_algo_t.  DGSP_AUTO here, where no features are known,
+ *             means: nnz-balanced, parallel reduction if N <= n_parallel_max,
+ *             else nnz-balanced sequential (the variants that are safe for
+ *             any row-length distribution).
+ *   stream    hipStream_t as void*, NULL = default stream.
+ *
+ * Every algo accepts every N >= 1 and any pointer alignment; vector loads of
+ * width v in {4, 2} are used when N % v == 0 and X, Y are 4v-byte aligned.
+ * M == 0 or N == 0: returns DGSP_OK without launching.  The number of stored
+ * entries is read on the device from rowptr[M]; the call never synchronises.
+ */
+int dgsp_spmm_csr(int64_t M, int64_t K, int64_t N,
+                  const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                  const float *X, float *Y, int algo, void *stream);
+
+/*
+ * Same operation with the number of stored entries supplied by the caller
+ * (nnz >= 0 must equal rowptr[M]; nnz < 0 means unknown and makes this call
+ * identical to dgsp_spmm_csr).  Knowing nnz lets the host size the launch to
+ * the work (small matrices get small grids) and pick the lanes-per-row of the
+ * row-split parallel kernel from nnz / M before the launch instead of inside
+ * the kernel.  The result is the same.
+ */
+int dgsp_spmm_csr_nnz(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                      const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                      const float *X, float *Y, int algo, void *stream);
+
+/*
+ * Adaptive call (Section 2.2): dgsp_select_algo(features, N), then the chosen
+ * kernel.  `features` is a host pointer, read before the call returns.  If
+ * `chosen` is not NULL it receives the dgsp_algo_t that ran.
+ */
+int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N,
+                       const dgsp_features_t *features,
+                       const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                       const float *X, float *Y, int *chosen, void *stream);
+
+/*
+ * Kernel-selection rules of Section 2.2 (Figure "Adaptive strategy to select
+ * kernels"): first N decides parallel vs sequential reduction, then avg_row
+ * (parallel side) or stdv_row / avg_row (sequential side) decides whether to
+ * balance by non-zeros.  Pure host function; returns a dgsp_algo_t in 0..3, or
+ * DGSP_AUTO (-1) if features is NULL or N < 1.
+ */
+int dgsp_select_algo(const dgsp_features_t *features, int64_t N);
+
+/* Read / replace the thresholds used by dgsp_select_algo (process-wide, not
+ * thread-safe against concurrent selection).  Host pointers. */
+void dgsp_get_thresholds(dgsp_thresholds_t *out);
+void dgsp_set_thresholds(const dgsp_thresholds_t *in);
+
+/*
+ * Row-length statistics from a HOST copy of rowptr (Section 2.2's "low-cost"
+ * features: one pass over M+1 integers, two accumulators).  Returns
+ * DGSP_ERR_INVALID_ARG if M < 0, a pointer is NULL, rowptr[0] != 0 or rowptr
+ * decreases.  M == 0 gives all-zero features.
+ */
+int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t *rowptr_host,
+                                   dgsp_features_t *out);
+
+/*
+ * Measurement aid, not part of the method: dst[i] = src[i] for i < n (device
+ * fp32 buffers, n >= 0), a plain streaming copy whose 8*n bytes calibrate the
+ * achievable HBM bandwidth and the profiler's byte counters.
+ */
+int dgsp_copy_f32(float *dst, const float *src, int64_t n, void *stream);
+
+/* Static strings; never NULL. */
+const char *dgsp_algo_name(int algo);
+const char *dgsp_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGSP_H */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding over ``libdgsp.so`` with the same names as the C-ABI
+(``include/dgsp.h``).  Argument marshalling only: every step of the
+multiplication runs inside the HIP library.  Tensors are ``torch`` CUDA(HIP)
+tensors used purely as device memory; the stream is torch's current stream.
+
+There is no CPU fallback: if the shared library has not been built the first
+call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+RS_SR, RS_PR, NB_SR, NB_PR, AUTO = 0, 1, 2, 3, -1
+ALGOS = (RS_SR, RS_PR, NB_SR, NB_PR)
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_LAUNCH = 0, 1, 2, 3
+
+LIB_PATH = Path(__file__).resolve().parent / "libdgsp.so"
+
+EXPORTS = (
+    "dgsp_spmm_csr", "dgsp_spmm_csr_nnz", "dgsp_spmm_csr_auto", "dgsp_select_algo",
+    "dgsp_get_thresholds", "dgsp_set_thresholds", "dgsp_features_from_rowptr_host",
+    "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
+)
+
+
+class Features(ctypes.Structure):
+    """``dgsp_features_t``"""
+    _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("avg_row", ctypes.c_double), ("stdv_row", ctypes.c_double), ("cv_row", ctypes.c_double),
+                ("max_row", ctypes.c_int64), ("min_row", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class Thresholds(ctypes.Structure):
+    """``dgsp_thresholds_t``"""
+    _fields_ = [("n_parallel_max", ctypes.c_int64), ("pr_avg_row_min", ctypes.c_double),
+                ("pr_cv_max", ctypes.c_double), ("sr_cv_min", ctypes.c_double)]
+
+
+class DgspError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (raises if it is missing: build it first with
+    ``python -m paper_2106_16064_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise DgspError(f"{LIB_PATH} is missing: run `python -m paper_2106_16064_amd.build` "
+                            "(there is no CPU fallback)")
+        L = ctypes.CDLL(str(LIB_PATH))
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.dgsp_spmm_csr.restype = ci
+        L.dgsp_spmm_csr.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.dgsp_spmm_csr_nnz.restype = ci
+        L.dgsp_spmm_csr_nnz.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.dgsp_spmm_csr_auto.restype = ci
+        L.dgsp_spmm_csr_auto.argtypes = [i64, i64, i64, ctypes.POINTER(Features), vp, vp, vp, vp, vp,
+                                         ctypes.POINTER(ci), vp]
+        L.dgsp_select_algo.restype = ci
+        L.dgsp_select_algo.argtypes = [ctypes.POINTER(Features), i64]
+        L.dgsp_get_thresholds.restype = None
+        L.dgsp_get_thresholds.argtypes = [ctypes.POINTER(Thresholds)]
+        L.dgsp_set_thresholds.restype = None
+        L.dgsp_set_thresholds.argtypes = [ctypes.POINTER(Thresholds)]
+        L.dgsp_features_from_rowptr_host.restype = ci
+        L.dgsp_features_from_rowptr_host.argtypes = [i64, i64, vp, ctypes.POINTER(Features)]
+        L.dgsp_copy_f32.restype = ci
+        L.dgsp_copy_f32.argtypes = [vp, vp, i64, vp]
+        L.dgsp_algo_name.restype = ctypes.c_char_p
+        L.dgsp_algo_name.argtypes = [ci]
+        L.dgsp_status_string.restype = ctypes.c_char_p
+        L.dgsp_status_string.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != OK:
+        raise DgspError(f"{what}: {dgsp_status_string(rc)} (status {rc})")
+
+
+def _ptr(t):
+    return None if t is None or t.numel() == 0 else t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y):
+    import torch
+    for name, t, dt in (("rowptr", rowptr, torch.int32), ("colidx", colidx, torch.int32),
+                        ("vals", vals, torch.float32), ("X", X, torch.float32), ("Y", Y, torch.float32)):
+        if not t.is_cuda or t.dtype != dt or not t.is_contiguous():
+            raise DgspError(f"{name} must be a contiguous {dt} tensor on the GPU")
+    if rowptr.numel() != M + 1 or colidx.numel() != vals.numel():
+        raise DgspError("rowptr needs M+1 entries; colidx and vals must have equal length")
+    if X.numel() != K * N or Y.numel() != M * N:
+        raise DgspError("X must hold K*N and Y M*N elements")
+
+
+def dgsp_spmm_csr(M, K, N, rowptr, colidx, vals, X, Y, algo, stream=None):
+    """``Y = A X`` with the kernel ``algo``; the entry count is read on the device."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    rc = lib().dgsp_spmm_csr(M, K, N, _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
+                             int(algo), _stream(stream))
+    _check(rc, "dgsp_spmm_csr")
+
+
+def dgsp_spmm_csr_nnz(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, stream=None):
+    """``Y = A X`` with the entry count given by the caller."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    if nnz >= 0 and colidx.numel() < nnz:
+        raise DgspError("colidx/vals shorter than nnz")
+    rc = lib().dgsp_spmm_csr_nnz(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
+                                 int(algo), _stream(stream))
+    _check(rc, "dgsp_spmm_csr_nnz")
+
+
+def dgsp_spmm_csr_auto(M, K, N, features: Features, rowptr, colidx, vals, X, Y, stream=None) -> int:
+    """Select by the rules, run, return the chosen algo."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    chosen = ctypes.c_int(-1)
+    rc = lib().dgsp_spmm_csr_auto(M, K, N, ctypes.byref(features), _ptr(rowptr), _ptr(colidx), _ptr(vals),
+                                  _ptr(X), _ptr(Y), ctypes.byref(chosen), _stream(stream))
+    _check(rc, "dgsp_spmm_csr_auto")
+    return chosen.value
+
+
+def dgsp_select_algo(features: Features, N: int) -> int:
+    return int(lib().dgsp_select_algo(ctypes.byref(features), int(N)))
+
+
+def dgsp_get_thresholds() -> Thresholds:
+    t = Thresholds()
+    lib().dgsp_get_thresholds(ctypes.byref(t))
+    return t
+
+
+def dgsp_set_thresholds(t: Thresholds) -> None:
+    lib().dgsp_set_thresholds(ctypes.byref(t))
+
+
+def dgsp_features_from_rowptr_host(M, K, rowptr_host) -> Features:
+    """``rowptr_host``: a contiguous int32 numpy array (or CPU tensor) of M+1 entries."""
+    import numpy as np
+    a = np.ascontiguousarray(rowptr_host, dtype=np.int32)
+    if a.size != M + 1:
+        raise DgspError("rowptr needs M+1 entries")
+    f = Features()
+    rc = lib().dgsp_features_from_rowptr_host(M, K, a.ctypes.data, ctypes.byref(f))
+    _check(rc, "dgsp_features_from_rowptr_host")
+    return f
+
+
+def dgsp_copy_f32(dst, src, n=None, stream=None):
+    n = dst.numel() if n is None else n
+    rc = lib().dgsp_copy_f32(_ptr(dst), _ptr(src), int(n), _stream(stream))
+    _check(rc, "dgsp_copy_f32")
+
+
+def dgsp_algo_name(algo: int) -> str:
+    return lib().dgsp_algo_name(int(algo)).decode()
+
+
+def dgsp_status_string(status: int) -> str:
+    return lib().dgsp_status_string(int(status)).decode()
+
+
+class DeviceCsr:
+    """A CSR matrix resident in GPU memory (plumbing for tests and benchmarks)."""
+
+    def __init__(self, A, device="cuda:0"):
+        import torch
+        self.M, self.K, self.nnz = A.M, A.K, A.nnz
+        self.rowptr = torch.from_numpy(A.rowptr).to(device)
+        self.colidx = torch.from_numpy(A.colidx).to(device)
+        self.vals = torch.from_numpy(A.vals).to(device)
+        self.features = dgsp_features_from_rowptr_host(A.M, A.K, A.rowptr)
+
+    def spmm(self, X, algo=AUTO, Y=None, use_nnz=True, stream=None):
+        """Y = A X.  ``algo=AUTO`` applies the selection rules to this matrix's features."""
+        import torch
+        N = X.shape[1] if X.dim() == 2 else 1
+        if Y is None:
+            Y = torch.empty((self.M, N), dtype=torch.float32, device=X.device)
+        if algo == AUTO:
+            dgsp_spmm_csr_auto(self.M, self.K, N, self.features, self.rowptr, self.colidx, self.vals, X, Y, stream)
+        elif use_nnz:
+            dgsp_spmm_csr_nnz(self.M, self.K, N, self.nnz, self.rowptr, self.colidx, self.vals, X, Y, algo, stream)
+        else:
+            dgsp_spmm_csr(self.M, self.K, N, self.rowptr, self.colidx, self.vals, X, Y, algo, stream)
+        return Y

@@ -1,0 +1,58 @@
+"""Builds ``libdgsp.so`` (HIP, gfx950) in place next to this file.
+
+Run as ``python -m paper_2106_16064_amd.build``.  hipcc cross-compiles without
+a GPU, so this works on any machine with ROCm installed.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+from pathlib import Path
+
+HERE = Path(__file__).resolve().parent
+CSRC = HERE / "csrc"
+LIB = HERE / "libdgsp.so"
+SOURCES = [CSRC / "dgsp.hip"]
+HEADERS = [CSRC / "dgsp_device.hpp", CSRC / "dgsp_kernels.hpp", HERE.parent / "include" / "dgsp.h"]
+
+HIPCC_FLAGS = [
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-munsafe-fp-atomics",                                      # native global_atomic_add_f32
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 instruction forms
+    "-Wno-unused-command-line-argument",
+]
+
+
+def hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found; libdgsp cannot be built")
+    return exe
+
+
+def build(verbose: bool = True, extra_flags=()) -> Path:
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", str(LIB), *map(str, SOURCES)]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    # the host pass does not know the packed-fp32 feature and says so; that is expected
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{err}")
+    if verbose and err.strip():
+        print(err, file=sys.stderr)
+    return LIB
+
+
+def is_stale() -> bool:
+    if not LIB.exists():
+        return True
+    t = LIB.stat().st_mtime
+    return any(f.stat().st_mtime > t for f in SOURCES + HEADERS)
+
+
+if __name__ == "__main__":
+    build()

