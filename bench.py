@@ -1,0 +1,343 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSR SpMV/SpMM hot path on one MI355X.
+
+Default run (what the driver calls):
+    python bench.py --gpus 1 --steps K --warmup W
+times K "steps" of the power-law SpMV configuration (R-MAT 2^20 vertices,
+average degree 16, N = 1).  One step = the whole hot path once: the selection
+rules on the matrix's precomputed row statistics, then the chosen kernel
+(through ``dgsp_spmm_csr_auto``).  Inputs are resident in device memory before
+the timed region; successive steps rotate over several copies of (A, X, Y) so
+that every step streams its operands from HBM rather than from the 256 MB
+Infinity Cache (one copy of this workload, ~141 MB, would fit).  Prints ONE
+JSON line.
+
+Other suites (for the numbers quoted in the design doc / profiles/, each still
+prints one JSON line and writes details under gpurun_out/):
+    --suite configs   every kernel on the R-MAT and stencil configurations
+    --suite sweep     the 24-matrix x 10-N selector sweep (loss vs best kernel)
+    --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+CACHE_BYTES = 256e6 + 32e6     # Infinity Cache + 8 x 4 MB L2: what rotation has to exceed
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on dgsp_copy_f32);
+# see profiles/.  None = not measured for that cell.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(A, N):
+    """Bytes the method has to move once: 8 per stored entry (column index and
+    value), rowptr, every touched row of X once, Y once."""
+    return 8 * A.nnz + 4 * (A.M + 1) + 4 * A.k_touched() * N + 4 * A.M * N
+
+
+_MATRIX_CACHE = {}
+
+
+def make_workload(name, n):
+    """(A, X, label) of a named benchmark configuration; A is cached per name."""
+    from paper_2106_16064_amd import workloads as wl
+    gens = {
+        "rmat_spmv": (lambda: wl.rmat_csr(20, 16, seed=0, values="uniform01"), "uniform",
+                      "power-law SpMV/SpMM: R-MAT 2^20 vertices, avg degree 16, U(0,1) values"),
+        "rmat_gnn": (lambda: wl.rmat_csr(20, 16, seed=0, values="rownorm"), "normal",
+                     "GNN-style SpMM: R-MAT 2^20 vertices, avg degree 16, row-normalised"),
+        "stencil": (lambda: wl.stencil27_csr(128, seed=0), "uniform", "27-point stencil on 128^3"),
+        "tiny": (lambda: wl.poisson_csr(4096, 4096, 8.0, seed=0), "uniform", "tiny SpMM: 4096^2 Poisson(8)"),
+    }
+    if name not in gens:
+        raise SystemExit(f"unknown workload {name}")
+    gen, xdist, label = gens[name]
+    if name not in _MATRIX_CACHE:
+        _MATRIX_CACHE.clear()          # one big matrix at a time on the host
+        _MATRIX_CACHE[name] = gen()
+    A = _MATRIX_CACHE[name]
+    return A, wl.dense_matrix(A.K, n, xdist, seed=0), f"{label}, N={n}"
+
+
+class Rotation:
+    """R device copies of (A, X, Y): step i uses copy i % R."""
+
+    def __init__(self, A, X, copies=None, device="cuda:0"):
+        import torch
+        from paper_2106_16064_amd import binding as dg
+        self.A, self.N = A, X.shape[1]
+        foot = algorithmic_bytes(A, self.N)
+        if copies is None:
+            copies = int(min(8, max(2, -(-3 * CACHE_BYTES // foot))))
+        self.copies = copies
+        base = dg.DeviceCsr(A, device)
+        self.mats = [base]
+        for _ in range(copies - 1):
+            m = dg.DeviceCsr.__new__(dg.DeviceCsr)
+            m.M, m.K, m.nnz, m.features = base.M, base.K, base.nnz, base.features
+            m.rowptr, m.colidx, m.vals = base.rowptr.clone(), base.colidx.clone(), base.vals.clone()
+            self.mats.append(m)
+        x0 = torch.from_numpy(X).to(device)
+        self.X = [x0] + [x0.clone() for _ in range(copies - 1)]
+        self.Y = [torch.empty((A.M, self.N), dtype=torch.float32, device=device) for _ in range(copies)]
+
+    def step(self, i, algo, warm=False):
+        j = 0 if warm else i % self.copies
+        self.mats[j].spmm(self.X[j], algo=algo, Y=self.Y[j])
+
+
+def time_steps(rot, algo, steps, warmup, warm=False):
+    """Wall-clock ms per step over `steps` back-to-back launches."""
+    import torch
+    for i in range(warmup):
+        rot.step(i, algo, warm)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        rot.step(i, algo, warm)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_events(fn_before, fn_timed, steps, warmup):
+    """Per-launch durations (ms) of fn_timed(i), bracketed by HIP events on the
+    launch stream; fn_before(i) runs untimed just before each launch."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i in range(warmup):
+        if fn_before:
+            fn_before(i)
+        fn_timed(i)
+    torch.cuda.synchronize()
+    for i in range(steps):
+        if fn_before:
+            fn_before(i)
+        evs[i][0].record()
+        fn_timed(i)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
+def median(v):
+    s = sorted(v)
+    return s[len(s) // 2]
+
+
+def copy_bandwidth(nbytes=1 << 30, reps=10):
+    """Achieved GB/s (read + write) of the plain streaming copy kernel."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    n = nbytes // 4
+    src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    ms = time_events(None, lambda i: dg.dgsp_copy_f32(dst, src, n), reps, 3)
+    return 2 * nbytes / (median(ms) * 1e-3) / 1e9
+
+
+def cpu_baseline(A, X, budget_s=8.0):
+    """The CPU oracle (test infrastructure, never tuned) on the same workload."""
+    import oracle
+    N = X.shape[1]
+    oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X, with_bound=False)   # warm-up, builds the .so
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_start < budget_s and len(times) < 200):
+        t0 = time.perf_counter()
+        oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X, with_bound=False)
+        times.append(time.perf_counter() - t0)
+    best = min(times)
+    return {"value": 2.0 * A.nnz * N / best / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(),
+            "kind": "oracle", "ms_per_pass": best * 1e3,
+            "effective_GBps": algorithmic_bytes(A, N) / best / 1e9,
+            "sample": f"the full workload ({A.nnz} stored entries, N={N}), best of {len(times)} passes of the "
+                      f"fp64 oracle incl. its input validation, OpenMP over rows"}
+
+
+def variant_table(rot, steps, warmup):
+    """Event-timed median ms of each of the four kernels on the rotation's workload."""
+    from paper_2106_16064_amd import binding as dg
+    out = {}
+    for algo in dg.ALGOS:
+        k = max(5, min(steps, 50))
+        ms = time_events(None, lambda i: rot.step(i, algo), k, 3)
+        out[dg.dgsp_algo_name(algo)] = median(ms)
+    return out
+
+
+# ---------------------------------------------------------------------------- suites
+def run_headline(args):
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    A, X, label = make_workload(args.workload or "rmat_spmv", args.n or 1)
+    N = X.shape[1]
+    rot = Rotation(A, X)
+    f = rot.mats[0].features
+    chosen = dg.dgsp_select_algo(f, N)
+
+    ms_cold = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=False)
+    ms_warm = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=True)
+
+    # dominant kernel alone: for the balanced kernels the small prepare launch runs untimed first
+    ev = time_events(None, lambda i: rot.step(i, chosen), args.steps, args.warmup)
+    ev_ms = sum(ev) / len(ev)
+
+    bytes_alg = algorithmic_bytes(A, N)
+    flops = 2.0 * A.nnz * N
+    table = variant_table(rot, args.steps, args.warmup)
+    best = min(table, key=table.get)
+    sel_name = dg.dgsp_algo_name(chosen)
+
+    # parity spot check of what was just timed
+    import oracle
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    ok, worst = oracle.within_bound(rot.Y[0].cpu().numpy(), yref, bnd, 1e-5)
+
+    achieved = bytes_alg / (ev_ms * 1e-3) / 1e9
+    out = {
+        "metric": "SpMM GFLOP/s (2*nnz*N/t); effective HBM GB/s and selector loss alongside",
+        "value": flops / (ms_cold * 1e-3) / 1e9, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_cold,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": label, "M": A.M, "K": A.K, "nnz": A.nnz, "N": N,
+                   "buffer_rotation": rot.copies, "selected_kernel": sel_name},
+        "effective_GBps": bytes_alg / (ms_cold * 1e-3) / 1e9,
+        "pct_hbm_peak": 100.0 * bytes_alg / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "warm_cache": {"ms_per_step": ms_warm, "GFLOPs": flops / (ms_warm * 1e-3) / 1e9,
+                       "effective_GBps": bytes_alg / (ms_warm * 1e-3) / 1e9},
+        "copy_kernel_GBps": copy_bandwidth(),
+        "selector": {"chosen": sel_name, "best": best, "loss_vs_best": table[sel_name] / table[best] - 1.0,
+                     "median_ms": table},
+        "parity": {"ok": ok, "worst_err_over_bound": worst, "tol": 1e-5},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{sel_name}/{args.workload or 'rmat_spmv'}/N{N}"),
+                     "kernel": f"{sel_name} (whole call, HIP events, mean of {len(ev)} launches)",
+                     "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms},
+        "cpu_baseline": cpu_baseline(A, X),
+    }
+    print(json.dumps(out))
+    return 0 if ok else 1
+
+
+def run_configs(args):
+    from paper_2106_16064_amd import binding as dg
+    os.makedirs("gpurun_out", exist_ok=True)
+    cells = [("rmat_spmv", 1), ("rmat_spmv", 2), ("rmat_spmv", 4), ("rmat_gnn", 32), ("rmat_gnn", 64),
+             ("rmat_gnn", 128), ("stencil", 1), ("stencil", 2), ("stencil", 4), ("stencil", 8)]
+    if args.workload:
+        cells = [c for c in cells if c[0] == args.workload]
+    rows = []
+    path = os.path.join("gpurun_out", args.out or "bench_configs.jsonl")
+    with open(path, "w") as fh:
+        for name, n in cells:
+            A, X, label = make_workload(name, n)
+            rot = Rotation(A, X)
+            table = variant_table(rot, args.steps, args.warmup)
+            sel = dg.dgsp_algo_name(dg.dgsp_select_algo(rot.mats[0].features, n))
+            best = min(table, key=table.get)
+            ba = algorithmic_bytes(A, n)
+            row = {"workload": label, "N": n, "nnz": A.nnz, "algorithmic_bytes": ba, "selected": sel, "best": best,
+                   "loss_vs_best": table[sel] / table[best] - 1.0,
+                   "kernels": {k: {"ms": v, "GFLOPs": 2.0 * A.nnz * n / v / 1e6, "GBps": ba / v / 1e6,
+                                   "pct_hbm_peak": 100 * ba / v / 1e6 / HBM_PEAK_GBS} for k, v in table.items()}}
+            rows.append(row)
+            fh.write(json.dumps(row) + "\n")
+            fh.flush()
+            print(f"[configs] {name} N={n}: " + ", ".join(f"{k} {v:.3f} ms" for k, v in table.items())
+                  + f" | selected {sel}, best {best}", file=sys.stderr, flush=True)
+            del rot
+    print(json.dumps({"suite": "configs", "cells": len(rows), "file": path}))
+    return 0
+
+
+def run_sweep(args):
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs("gpurun_out", exist_ok=True)
+    path = os.path.join("gpurun_out", args.out or "bench_sweep.jsonl")
+    M = args.sweep_m
+    losses = []
+    with open(path, "w") as fh:
+        for A in wl.sweep_matrices(M):
+            for n in wl.SWEEP_NS:
+                X = wl.dense_matrix(A.K, n, "uniform", seed=0)
+                rot = Rotation(A, X, copies=2)
+                table = variant_table(rot, args.steps, args.warmup)
+                f = rot.mats[0].features
+                sel = dg.dgsp_algo_name(dg.dgsp_select_algo(f, n))
+                best = min(table, key=table.get)
+                loss = table[sel] / table[best] - 1.0
+                losses.append(loss)
+                fh.write(json.dumps({"matrix": A.name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row,
+                                     "max_row": f.max_row, "nnz": A.nnz, "ms": table, "selected": sel,
+                                     "best": best, "loss": loss}) + "\n")
+                fh.flush()
+                del rot
+            print(f"[sweep] {A.name} done", file=sys.stderr, flush=True)
+    losses.sort()
+    print(json.dumps({"suite": "sweep", "cells": len(losses), "mean_loss": sum(losses) / len(losses),
+                      "median_loss": losses[len(losses) // 2], "max_loss": losses[-1], "file": path}))
+    return 0
+
+
+def run_kernel(args):
+    """One kernel in a plain loop, for rocprofv3."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    A, X, label = make_workload(args.workload or "rmat_spmv", args.n or 1)
+    rot = Rotation(A, X, copies=1 if args.warm else None)
+    algo = {"rs_sr": 0, "rs_pr": 1, "nb_sr": 2, "nb_pr": 3, "auto": -1}[args.algo]
+    ms = time_steps(rot, algo, args.steps, args.warmup, warm=args.warm)
+    if args.copy_calibration:
+        n = 1 << 28
+        src = torch.zeros(n, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dg.dgsp_copy_f32(dst, src, n)
+        torch.cuda.synchronize()
+    print(json.dumps({"suite": "kernel", "workload": label, "algo": args.algo, "ms_per_step": ms,
+                      "algorithmic_bytes": algorithmic_bytes(A, X.shape[1]), "copies": rot.copies}))
+    return 0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "kernel"])
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--n", type=int, default=None)
+    ap.add_argument("--algo", default="auto")
+    ap.add_argument("--warm", action="store_true", help="kernel suite: reuse one buffer set (cache-warm)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="kernel suite: also run five 1 GiB dgsp_copy_f32 launches (byte-counter calibration)")
+    ap.add_argument("--sweep-m", type=int, default=1 << 18)
+    ap.add_argument("--out", default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        return 2
+    from paper_2106_16064_amd import binding as dg
+    dg.lib()
+    return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "kernel": run_kernel}[args.suite](args)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

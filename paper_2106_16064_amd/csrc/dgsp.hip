@@ -57,11 +57,6 @@ inline unsigned clamp_blocks(long long want, long long cap) {
 // resident waves per CU assumed when sizing machine-filling grids
 constexpr int kBlocksPerCu = 8;
 
-// tile sizes of the balanced kernels (entries per wave and tile)
-constexpr int kNbPrChunks = 4;                       // 4 x 64 entries
-constexpr int kNbPrTile = kWave * kNbPrChunks;
-constexpr int kNbPrLogTile = 8;
-static_assert((1 << kNbPrLogTile) == kNbPrTile, "tile must be a power of two");
 static_assert((1 << kNbSrLogTile) == kNbSrTile, "tile must be a power of two");
 
 struct Problem {
@@ -121,33 +116,42 @@ int launch_rs_sr(const Problem& p) {
 }
 
 // ---------------------------------------------------------------- balanced launches
-int launch_prepare(const Problem& p, int logU) {
+// `unit` > 0: rows split by a multiple of `unit` merge-path items are zeroed;
+// unit == 0: the unit is the per-wave share of tiles of W items on nwaves waves.
+int launch_prepare(const Problem& p, unsigned unit, unsigned W, unsigned nwaves) {
     int logP = ilog2_ceil(p.N);
     if (logP > 6) logP = 6;
     const long long threads = (long long)p.M << logP;
     const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, logU, logP);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, W, nwaves, logP);
     return DGSP_OK;
 }
 
+// blocks of a machine-filling grid whose waves share nnz + M merge-path items in tiles of `tile`
 inline unsigned balanced_blocks(const Problem& p, int tile) {
     const long long cap = (long long)device_info().cus * kBlocksPerCu;
     if (p.nnz < 0) return (unsigned)cap;
-    const long long tiles = (p.nnz + tile - 1) / tile;
+    const long long tiles = (p.nnz + p.M + tile - 1) / tile;
     return clamp_blocks((tiles + kWavesPerBlock - 1) / kWavesPerBlock, cap);
 }
 
-int launch_nb_pr(const Problem& p) {
-    const int V = vector_width(p.N, p.X, p.Y);
-    if (int rc = launch_prepare(p, kNbPrLogTile)) return rc;
-    if (p.nnz == 0) return DGSP_OK;
-    const dim3 grid(balanced_blocks(p, kNbPrTile));
-    switch (V) {
-        case 4: DGSP_LAUNCH((nb_pr_kernel<4, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
-        case 2: DGSP_LAUNCH((nb_pr_kernel<2, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
-        default: DGSP_LAUNCH((nb_pr_kernel<1, kNbPrChunks>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y); break;
-    }
+template <int V, int KQ>
+int launch_nb_pr_v(const Problem& p) {
+    constexpr int W = kWave * 4 * KQ;
+    const unsigned col_groups = (unsigned)(p.N / V);
+    if (col_groups > 65535u) return DGSP_ERR_INVALID_ARG;
+    const dim3 grid(balanced_blocks(p, W), col_groups);
+    if (int rc = launch_prepare(p, 0, W, grid.x * kWavesPerBlock)) return rc;
+    DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
+}
+
+int launch_nb_pr(const Problem& p) {
+    switch (vector_width(p.N, p.X, p.Y)) {
+        case 4: return launch_nb_pr_v<4, 1>(p);
+        case 2: return launch_nb_pr_v<2, 2>(p);
+        default: return launch_nb_pr_v<1, 2>(p);
+    }
 }
 
 int launch_nb_sr(const Problem& p) {
@@ -156,9 +160,8 @@ int launch_nb_sr(const Problem& p) {
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
-    const int logU = kNbSrLogTile - 6 + logG;   // entries per lane-group run
-    if (int rc = launch_prepare(p, logU)) return rc;
-    if (p.nnz == 0) return DGSP_OK;
+    const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
+    if (int rc = launch_prepare(p, 1u << logU, 0, 0)) return rc;
     const dim3 grid(balanced_blocks(p, kNbSrTile), col_blocks);
     switch (V) {
         case 4: DGSP_LAUNCH(nb_sr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;

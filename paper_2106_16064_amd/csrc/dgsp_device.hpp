@@ -118,6 +118,7 @@ __device__ __forceinline__ float dpp_or_zero(float v) {
 
 constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
 constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+constexpr int kDppWaveShr1 = 0x138;   // lane l reads lane l-1 across the whole wave; lane 0 gets the fill value
 
 // `width` (wave-uniform, a power of two <= 64) promises h < width, which lets
 // the steps with d >= width be skipped by a scalar branch.
@@ -155,106 +156,22 @@ __device__ __forceinline__ void segmented_scan(float (&v)[V], int h, int lane, i
     }
 }
 
-// ---------------------------------------------------------------------------
-// locating CSR rows from positions (nnz-balanced kernels)
-// ---------------------------------------------------------------------------
-//
-// The paper's balanced kernels refer "to the row indices of each element"
-// (Section 2.1.1) without saying where they come from.  The ABI passes only
-// rowptr, so rows are found by searching it.
-
-// Largest row r in [0, M) with rowptr[r] <= pos.  Needs rowptr[0] <= pos <
-// rowptr[M].  All 64 lanes probe at once, so each round divides the range by
-// 64: four rounds for a million rows.  Result is wave-uniform.
-__device__ __forceinline__ int wave_find_row(const int* __restrict__ rowptr, int M, unsigned pos, int lane) {
-    int lo = 0, hi = M;   // invariant: rowptr[lo] <= pos < rowptr[hi]
-    while (hi - lo > 1) {
-        const int span = hi - lo;
-        const int step = (span + 63) >> 6;
-        int idx = lo + lane * step;
-        idx = idx < hi ? idx : hi;
-        const unsigned v = (unsigned)rowptr[idx];
-        const unsigned long long below = __ballot(v <= pos);   // 1...10...0, lane 0 always set
-        int cnt = __popcll(below);
-        cnt = cnt > 0 ? cnt : 1;                               // only a malformed rowptr gives 0
-        const int nlo = lo + (cnt - 1) * step;
-        int nhi = lo + cnt * step;
-        nhi = nhi < hi ? nhi : hi;
-        lo = nlo;
-        hi = nhi;
-    }
-    return uniform(lo);
+// Inclusive running maximum over the lanes of a wave (same DPP network, no
+// segments): lane l gets max(v[0..l]).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned dpp_or_zero_u(unsigned v) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
 
-// A wave's view of the row starts that follow row `r_lo`:
-//   entry i  ==  rowptr[min(r_lo + 1 + i, M)]
-// kept in LDS (`win`, WMAX ints) when the first `wlen` entries already reach
-// past the end of the tile (`covered`), else read from global memory.
-struct RowWindow {
-    const int* __restrict__ rowptr;
-    const int* win;    // LDS
-    int M;
-    int r_lo;          // wave-uniform; rowptr[r_lo] <= first position of the tile
-    unsigned rs_lo;    // rowptr[r_lo]
-    int wlen;          // entries valid in win (multiple of 64)
-    bool covered;      // win[wlen-1] >= tile end
-
-    __device__ __forceinline__ unsigned entry(int i) const {
-        if (covered) return (unsigned)win[i];
-        long long r = (long long)r_lo + 1 + i;
-        return (unsigned)rowptr[r < M ? r : M];
-    }
-
-    // For a position p inside the tile: cnt = number of entries <= p, so that
-    // p lies in row r_lo + cnt, which spans [rs, re).
-    __device__ __forceinline__ void locate(unsigned p, int& cnt, unsigned& rs, unsigned& re) const {
-        int c = 0;
-        if (covered) {
-            // branch-free upper bound over win[0, wlen); win[wlen-1] > p
-            for (int s = 256; s >= 64; s >>= 1) {           // only when the window grew past 64
-                if (s < wlen) { if (c + s - 1 < wlen && (unsigned)win[c + s - 1] <= p) c += s; }
-            }
-#pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) {
-                if ((unsigned)win[c + s - 1] <= p) c += s;
-            }
-            rs = c ? (unsigned)win[c - 1] : rs_lo;
-            re = (unsigned)win[c];
-        } else {
-            // first index in (r_lo, M] whose row start exceeds p; rowptr[M] = nnz > p
-            int lo = r_lo + 1, hi = M;
-            while (lo < hi) {
-                const int mid = lo + ((hi - lo) >> 1);
-                if ((unsigned)rowptr[mid] <= p) lo = mid + 1; else hi = mid;
-            }
-            c = lo - 1 - r_lo;
-            rs = (unsigned)rowptr[lo - 1];
-            re = (unsigned)rowptr[lo];
-        }
-        cnt = c;
-    }
-};
-
-// Fills the LDS window for the tile [ts, te) (all lanes of the wave call
-// this).  WMAX is a multiple of 64, at most 512.
-template <int WMAX>
-__device__ __forceinline__ RowWindow build_row_window(const int* __restrict__ rowptr, int M, int* win,
-                                                      int r_lo, unsigned rs_lo, unsigned te, int lane) {
-    RowWindow w;
-    w.rowptr = rowptr; w.win = win; w.M = M; w.r_lo = r_lo; w.rs_lo = rs_lo;
-    int wlen = 0;
-    bool covered;
-    wave_lds_sync();   // the previous tile's readers are done with `win`
-    do {
-        long long r = (long long)r_lo + 1 + wlen + lane;
-        const int v = rowptr[r < M ? r : M];
-        win[wlen + lane] = v;
-        wlen += kWave;
-        covered = (unsigned)read_lane(v, kWave - 1) >= te;
-    } while (!covered && wlen < WMAX);
-    wave_lds_sync();
-    w.wlen = wlen; w.covered = covered;
-    return w;
+__device__ __forceinline__ unsigned wave_max_scan(unsigned v) {
+    unsigned t;
+    t = dpp_or_zero_u<kDppRowShr1, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero_u<kDppRowShr2, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero_u<kDppRowShr4, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero_u<kDppRowShr8, 0xf>(v); v = t > v ? t : v;
+    t = dpp_or_zero_u<kDppRowBcast15, 0xa>(v); v = t > v ? t : v;
+    t = dpp_or_zero_u<kDppRowBcast31, 0xc>(v); v = t > v ? t : v;
+    return v;
 }
 
 }  // namespace dgsp

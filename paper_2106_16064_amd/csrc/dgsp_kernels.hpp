@@ -179,165 +179,288 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
 // nnz-balanced kernels: common partition
 // ===========================================================================
 //
-// The stored entries [0, nnz) are cut into tiles of T consecutive entries; the
-// tiles are dealt to the waves of the grid in contiguous ranges (wave w owns
-// tiles [w*tpw, (w+1)*tpw)), XCD-contiguously.  A wave finds the row of its
-// first entry once (wave_find_row) and then only walks forward.
+// The paper gives each warp "a fixed number of non-zeros" (Section 2.1.1).
+// Counting only stored entries leaves one hole: a stretch of (nearly) empty
+// rows puts an unbounded number of row boundaries into one share.  So the
+// unit of work here is the *item* of the merge path of Merrill & Garland, which the
+// paper cites as the fine-grained way to balance (Section 1): the list
+//     entries of row 0, end of row 0, entries of row 1, end of row 1, ...
+// has nnz + M items; row r's entries sit at diagonals
+// [r + rowptr[r], r + rowptr[r+1]) and its end marker at r + rowptr[r+1].
+// Cutting that list into equal pieces bounds both the entries and the rows
+// of a piece.  For matrices without empty stretches it is the paper's fixed
+// share of non-zeros up to the few percent that row markers add.
 //
-// Rows that end up split between tiles (or, in the sequential kernel, between
-// the runs of different lane groups) are combined with fp32 atomic adds; the
-// paper does not say how partial rows of different warps meet.  That needs
-// zeros underneath, and rows without entries need zeros too, so a small
-// "prepare" kernel runs first: it zeroes exactly the rows that are empty or
-// that cross a multiple of the unit U = 2^logU, and nothing else.  Rows that
-// lie inside one unit are written once, with a plain store.
+// Tiles of W items are dealt to the waves in contiguous ranges (XCD-contiguous
+// again); a wave finds its first row once with a 64-way search and then walks.
+//
+// Rows whose items straddle a partition boundary are combined with fp32
+// atomic adds (the paper does not say how partial rows of different warps
+// meet), which needs zeros underneath.  A small "prepare" kernel zeroes
+// exactly those rows and no others; every other row, empty ones included, is
+// written once with a plain store by the tile that holds its end marker.
 
+__device__ __forceinline__ unsigned merge_items_per_wave(unsigned items, unsigned W, unsigned nwaves) {
+    const unsigned ntiles = items / W + (items % W != 0);
+    const unsigned tpw = ntiles / nwaves + (ntiles % nwaves != 0);
+    return tpw * W;
+}
+
+// Zeroes the rows that are split by a multiple of `unit` items.  unit == 0
+// means "derive it from the wave partition" (items per wave for tiles of W
+// items on nwaves waves).  2^logP consecutive threads share a row.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
-                                                             float* __restrict__ Y, int logU, int logP) {
-    // 2^logP consecutive threads share a row and stride over its N columns
+                                                             float* __restrict__ Y, unsigned unit, unsigned W,
+                                                             unsigned nwaves, int logP) {
     const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
     const long long row = t >> logP;
     if (row >= M) return;
-    const unsigned rs = (unsigned)rowptr[row], re = (unsigned)rowptr[row + 1];
-    const bool split = (rs == re) || ((rs >> logU) != ((re - 1) >> logU));
-    if (!split) return;
+    if (unit == 0) unit = merge_items_per_wave((unsigned)rowptr[M] + (unsigned)M, W, nwaves);
+    const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
+    const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
+    if (first / unit == last / unit) return;
     float* y = Y + (size_t)row * N;
     for (int n = (int)(t & ((1 << logP) - 1)); n < N; n += 1 << logP) y[n] = 0.0f;
 }
 
-struct TileRange {
-    unsigned first, last;   // tiles [first, last)
-    unsigned nnz;
+// Number of rows whose end marker lies before diagonal d, i.e. rows r with
+// r + rowptr[r+1] < d (that key is strictly increasing in r).  64-way search,
+// wave-uniform result.
+__device__ __forceinline__ int wave_merge_rows_before(const int* __restrict__ rowptr, int M, unsigned d, int lane) {
+    int lo = 0, hi = M;   // rows < lo end before d; rows >= hi do not
+    while (hi > lo) {
+        const int span = hi - lo;
+        const int step = (span + 63) >> 6;
+        const long long r = (long long)lo + (long long)lane * step;
+        bool before = false;
+        if (r < hi) before = (unsigned)r + (unsigned)rowptr[r + 1] < d;
+        const int cnt = __popcll(__ballot(before));   // probes are monotone: 1...10...0
+        if (cnt == 0) {
+            hi = lo;
+        } else {
+            const int nlo = lo + (cnt - 1) * step + 1;
+            const int nhi = lo + cnt * step;
+            lo = nlo;
+            hi = nhi < hi ? nhi : hi;
+        }
+    }
+    return uniform(lo);
+}
+
+struct MergeRange {
+    unsigned nnz, items;
+    unsigned d0, d1;      // my diagonals [d0, d1)
 };
 
-template <int T>
-__device__ __forceinline__ TileRange my_tiles(const int* __restrict__ rowptr, int M) {
-    TileRange r;
+template <int W>
+__device__ __forceinline__ MergeRange my_merge_range(const int* __restrict__ rowptr, int M) {
+    MergeRange r;
     r.nnz = (unsigned)rowptr[M];
-    const unsigned ntiles = r.nnz / T + (r.nnz % T != 0);
+    r.items = r.nnz + (unsigned)M;
     const unsigned nwaves = gridDim.x * kWavesPerBlock;
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
-    const unsigned tpw = ntiles / nwaves + (ntiles % nwaves != 0);
-    const unsigned long long f = (unsigned long long)gw * tpw;
-    r.first = f < ntiles ? (unsigned)f : ntiles;
-    r.last = f + tpw < ntiles ? (unsigned)(f + tpw) : ntiles;
+    const unsigned per = merge_items_per_wave(r.items, W, nwaves);
+    const unsigned long long a = (unsigned long long)gw * per;
+    r.d0 = a < r.items ? (unsigned)a : r.items;
+    r.d1 = a + per < r.items ? (unsigned)(a + per) : r.items;
     return r;
 }
+
+constexpr unsigned kNoRow = 0xffffffffu;
+
+typedef int int4u __attribute__((ext_vector_type(4), aligned(4)));       // dwordx4 at dword alignment
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
 
 // ===========================================================================
 // nnz-balanced, parallel reduction: vectorized segment reduction (Section 2.1.1)
 // ===========================================================================
 //
-// Tile = KCH chunks of 64 entries.  In chunk j lane l holds entry
-// ts + 64*j + l (coalesced dword loads), gathers V dense values, multiplies,
-// and the chunk is reduced with the segmented DPP scan.  The last lane of a
-// segment "dumps" the row's sum (the paper words this as comparing with the
-// neighbour lane; here the lane compares its position with its row's end,
-// which it knows from the row search).  A row running from chunk j into
-// chunk j+1 hands its partial sum over in a register (lane 63 -> lane 0),
-// so atomics are needed only where a row crosses the tile.
+// Tile = W = 64*E items, E = 4*KQ.  Lane l owns the E consecutive entries
+// js + E*l ... of the tile (one or two dwordx4 loads per array), gathers V
+// dense values per entry, multiplies, and first reduces its own entries in
+// order.  Row ends are scattered into LDS as "row i ends after entry q"
+// marks, so a lane sees its boundaries with one 16-byte LDS read.  A lane
+// without a boundary contributes its whole sum to the row that is open
+// across lanes; a lane with boundaries closes that open row with its leading
+// part, stores the rows that lie inside it, and opens a new segment with its
+// trailing part.  The open row's running sum across lanes is the paper's
+// segment reduction: the wave64 DPP scan whose operator is "add unless a row
+// boundary lies in between".  The sum that is still open at the end of a
+// tile is handed to the wave's next tile in a register; only the two ends
+// of a wave's range can need an atomic add.
+// blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
-template <int V, int KCH>
+template <int V, int KQ>
 __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y) {
-    constexpr int T = kWave * KCH;
-    constexpr int WMAX = T < 512 ? T : 512;
-    __shared__ int s_win[kWavesPerBlock][WMAX];
+    constexpr int E = 4 * KQ;
+    constexpr int W = kWave * E;
+    __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W] = "ends before the tile's first entry"
     const int lane = lane_id();
-    int* win = s_win[wave_in_block()];
+    unsigned* bnd = s_bnd[wave_in_block()];
+    const int n0 = blockIdx.y * V;
 
-    const TileRange tr = my_tiles<T>(rowptr, M);
-    if (tr.first >= tr.last) return;
-    const unsigned nnz = tr.nnz;
+    const MergeRange mr = my_merge_range<W>(rowptr, M);
+    if (mr.d0 >= mr.d1) return;
+    const unsigned nnz = mr.nnz;
 
-    int r_lo = wave_find_row(rowptr, M, tr.first * (unsigned)T, lane);
-    unsigned rs_lo = (unsigned)rowptr[r_lo];
+    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);   // rows that ended before my range
+    unsigned js = mr.d0 - (unsigned)is;                        // entries consumed before my range
+    // the first row to end in my range started before it?  then its sum is shared with another wave
+    const int r_first = is;
+    const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < mr.d0;
 
-    for (unsigned tile = tr.first; tile < tr.last; ++tile) {
-        const unsigned ts = tile * (unsigned)T;
-        const unsigned te = (nnz - ts > (unsigned)T) ? ts + T : nnz;
+    auto close_row = [&](int row, const float (&val)[V]) {
+        float* y = Y + (size_t)row * N + n0;
+        if (first_split && row == r_first) atomic_add_vec<V>(y, val); else store_vec<V>(y, val);
+    };
 
-        // sparse entries first, so their latency overlaps the row search
-        int c[KCH]; float a[KCH];
+    float carry[V];      // running sum of the row that is open at the tile boundary (wave-uniform)
 #pragma unroll
-        for (int j = 0; j < KCH; ++j) {
-            const unsigned p = ts + j * kWave + lane;
-            const bool ok = p < te;
-            c[j] = ok ? stream_load(colidx + p) : -1;
-            a[j] = ok ? stream_load(vals + p) : 0.0f;
-        }
+    for (int i = 0; i < V; ++i) carry[i] = 0.0f;
 
-        const RowWindow w = build_row_window<WMAX>(rowptr, M, win, r_lo, rs_lo, te, lane);
-        int cnt[KCH]; unsigned rs[KCH], re[KCH];
-#pragma unroll
-        for (int j = 0; j < KCH; ++j) {
-            unsigned p = ts + j * kWave + lane;
-            p = p < te ? p : te - 1;
-            w.locate(p, cnt[j], rs[j], re[j]);
-        }
+    for (unsigned ds = mr.d0; ds < mr.d1; ds += W) {
+        const unsigned de = (mr.d1 - ds > (unsigned)W) ? ds + W : mr.d1;
 
-        for (int n0 = 0; n0 < N; n0 += V) {
-            float carry[V];
+        // ---- sparse entries (at most W of them; the tile's real count is known later)
+        int c[E]; float a[E];
 #pragma unroll
-            for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+        for (int k = 0; k < KQ; ++k) {
+            const unsigned p = js + (unsigned)(E * lane + 4 * k);
+            if (p + 4 <= nnz) {
+                const int4u cv = __builtin_nontemporal_load(reinterpret_cast<const int4u*>(colidx + p));
+                const float4u av = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(vals + p));
+                c[4 * k] = cv.x; c[4 * k + 1] = cv.y; c[4 * k + 2] = cv.z; c[4 * k + 3] = cv.w;
+                a[4 * k] = av.x; a[4 * k + 1] = av.y; a[4 * k + 2] = av.z; a[4 * k + 3] = av.w;
+            } else {
 #pragma unroll
-            for (int j = 0; j < KCH; ++j) {
-                const unsigned cs = ts + j * kWave;           // chunk [cs, ce)
-                if (cs >= te) break;                          // wave-uniform
-                const unsigned ce = (te - cs > (unsigned)kWave) ? cs + kWave : te;
-                const unsigned p = cs + lane;
-                const bool ok = p < te;
-                float v[V];
-                if (ok) {
-                    load_vec<V>(X + (size_t)c[j] * N + n0, v);
-#pragma unroll
-                    for (int i = 0; i < V; ++i) v[i] *= a[j];
-                } else {
-#pragma unroll
-                    for (int i = 0; i < V; ++i) v[i] = 0.0f;
-                }
-                if (lane == 0) {
-#pragma unroll
-                    for (int i = 0; i < V; ++i) v[i] += carry[i];
-                }
-                const unsigned seg_lo = rs[j] > cs ? rs[j] : cs;
-                const int h = ok ? (int)(p - seg_lo) : 0;
-                segmented_scan<V>(v, h, lane);
-
-                const unsigned seg_hi = re[j] < ce ? re[j] : ce;
-                const bool tail = ok && (p + 1 == seg_hi);
-                // does the last lane's row go on in the next chunk of this tile?
-                const bool cont = (ce < te) && ((unsigned)read_lane((int)re[j], kWave - 1) > ce);
-#pragma unroll
-                for (int i = 0; i < V; ++i) carry[i] = cont ? read_lane(v[i], kWave - 1) : 0.0f;
-                if (tail && !(cont && lane == kWave - 1)) {
-                    float* y = Y + (size_t)((long long)r_lo + cnt[j]) * N + n0;
-                    if (rs[j] >= ts && re[j] <= te) store_vec<V>(y, v);
-                    else atomic_add_vec<V>(y, v);
+                for (int u = 0; u < 4; ++u) {
+                    const bool ok = p + u < nnz;
+                    c[4 * k + u] = ok ? colidx[p + u] : 0;
+                    a[4 * k + u] = ok ? vals[p + u] : 0.0f;
                 }
             }
         }
 
-        // the row holding the tile's last entry is a lower bound for the next tile
-        int lc; unsigned lrs, lre;
-        w.locate(te - 1, lc, lrs, lre);
-        r_lo = uniform(r_lo + lc);
-        rs_lo = (unsigned)uniform((int)lrs);
+        // ---- row ends of this tile -> LDS marks
+        wave_lds_sync();                                   // the previous tile's readers are done
+#pragma unroll
+        for (int k = 0; k < KQ; ++k)
+            *reinterpret_cast<uint4*>(bnd + E * lane + 4 * k) = make_uint4(kNoRow, kNoRow, kNoRow, kNoRow);
+        if (lane == 0) bnd[W] = kNoRow;
+        wave_lds_sync();
+        int ie = is;
+        for (int m = 0; m < E; ++m) {                      // a tile holds at most W row ends
+            const long long r = (long long)is + m * kWave + lane;
+            bool ends = false;
+            if (r < M) {
+                const unsigned e = (unsigned)rowptr[r + 1];
+                ends = (unsigned)r + e < de;               // the row's end marker is inside the tile
+                if (ends) {
+                    const unsigned q = e - js;             // it ends after entry q-1 of the tile
+                    atomicMin(bnd + (q ? q - 1 : (unsigned)W), (unsigned)(r - is));
+                    // empty rows other than the tile's first get their zeros here: no sum ever closes them
+                    if (r > is && (unsigned)rowptr[r] == e) {
+                        float zero[V];
+#pragma unroll
+                        for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+                        store_vec<V>(Y + (size_t)r * N + n0, zero);
+                    }
+                }
+            }
+            const int cnt = __popcll(__ballot(ends));
+            ie += cnt;
+            if (cnt < kWave) break;
+        }
+        const unsigned je = de - (unsigned)ie;             // entries [js, je) belong to the tile
+        const int nE = (int)(je - js);
+        wave_lds_sync();
+
+        // ---- rows that end before the tile's first entry take the sum carried in
+        const unsigned b_in = bnd[W];
+        if (b_in != kNoRow) {
+            if (lane == 0) close_row(is + (int)b_in, carry);
+#pragma unroll
+            for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+        }
+
+        // ---- my boundaries, gather, products, in-lane reduction
+        unsigned b[E];
+#pragma unroll
+        for (int k = 0; k < KQ; ++k) {
+            const uint4 t = *reinterpret_cast<const uint4*>(bnd + E * lane + 4 * k);
+            b[4 * k] = t.x; b[4 * k + 1] = t.y; b[4 * k + 2] = t.z; b[4 * k + 3] = t.w;
+        }
+        float x[E][V];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (E * lane + e < nE) load_vec<V>(X + (size_t)c[e] * N + n0, x[e]);
+            else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) x[e][i] = 0.0f;
+                a[e] = 0.0f;
+            }
+        }
+        float s[V], head[V];
+        unsigned head_row = kNoRow;                        // kNoRow: no boundary inside this lane
+#pragma unroll
+        for (int i = 0; i < V; ++i) { s[i] = lane == 0 ? carry[i] : 0.0f; head[i] = 0.0f; }
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) s[i] = fmaf(a[e], x[e][i], s[i]);
+            if (b[e] != kNoRow) {
+                if (head_row == kNoRow) {
+                    head_row = b[e];
+#pragma unroll
+                    for (int i = 0; i < V; ++i) head[i] = s[i];
+                } else {
+                    close_row(is + (int)b[e], s);          // a row that begins and ends inside this lane
+                }
+#pragma unroll
+                for (int i = 0; i < V; ++i) s[i] = 0.0f;
+            }
+        }
+
+        // ---- the open row across lanes: segments start at lanes that hold a boundary
+        const bool flagged = head_row != kNoRow;
+        const int head_lane = (int)wave_max_scan(flagged ? (unsigned)lane : 0u);
+        segmented_scan<V>(s, lane - head_lane, lane);      // s: sum of the open row up to and including my lane
+        if (__ballot(flagged)) {                           // wave-uniform
+            float closing[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) closing[i] = dpp_or_zero<kDppWaveShr1, 0xf>(s[i]) + head[i];
+            if (flagged) close_row(is + (int)head_row, closing);
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) carry[i] = read_lane(s[i], kWave - 1);
+
+        is = ie;
+        js = je;
     }
+
+    // the row still open at the end of my range is finished by another wave
+    bool any = false;
+#pragma unroll
+    for (int i = 0; i < V; ++i) any |= carry[i] != 0.0f;
+    if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * N + n0, carry);
 }
 
 // ===========================================================================
 // nnz-balanced, sequential reduction with LDS-staged tiles (Sections 2.1.3, 1)
 // ===========================================================================
 //
-// A wave stages a tile of kNbSrTile entries in LDS with coalesced loads, then
-// its 64/G lane groups each walk one run of U = kNbSrTile*G/64 consecutive
-// entries.  Lane gl of a group owns V dense columns; per entry the group
-// reads one contiguous piece of a row of X.  When the walk reaches the next
-// row start the accumulator is flushed: plain store if the row lies inside
-// the run, atomic add if it crosses the run's ends (prepare kernel, U).
+// A wave stages a tile of W = 512 merge-path items in LDS: its entries
+// (colidx, val) with coalesced loads (coalesced sparse-row caching) and the
+// end offsets of the rows that end in it.  Its 64/G lane groups then each walk
+// one run of U = W*G/64 consecutive items in order; lane gl of a group owns V
+// dense columns, so per entry a group reads one contiguous piece of a row of
+// X.  At a row end the accumulator is flushed: plain store if the row's items
+// all lie in the run, atomic add otherwise (prepare kernel, unit U).  Empty
+// rows flush a zero accumulator, which is how they get their zeros.
+// blockIdx.y selects the block of G*V dense columns.
 
 constexpr int kNbSrTile = 512;
 constexpr int kNbSrLogTile = 9;
@@ -348,15 +471,15 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG) {
-    constexpr int T = kNbSrTile;
-    __shared__ int s_col[kWavesPerBlock][T];
-    __shared__ float s_val[kWavesPerBlock][T];
-    __shared__ int s_win[kWavesPerBlock][T];
+    constexpr int W = kNbSrTile;
+    __shared__ int s_col[kWavesPerBlock][W];
+    __shared__ float s_val[kWavesPerBlock][W];
+    __shared__ unsigned s_end[kWavesPerBlock][W + 4];   // end offsets of the rows ending in the tile
     const int lane = lane_id();
     const int wib = wave_in_block();
     int* cc = s_col[wib];
     float* cv = s_val[wib];
-    int* win = s_win[wib];
+    unsigned* ends = s_end[wib];
 
     const int G = 1 << logG;
     const int gl = lane & (G - 1);
@@ -366,42 +489,86 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
     const long long n = ((long long)blockIdx.y * G + gl) * V;
     const bool col_ok = n < N;
 
-    const TileRange tr = my_tiles<T>(rowptr, M);
-    if (tr.first >= tr.last) return;
-    const unsigned nnz = tr.nnz;
+    const MergeRange mr = my_merge_range<W>(rowptr, M);
+    if (mr.d0 >= mr.d1) return;
+    const unsigned nnz = mr.nnz;
 
-    int r_lo = wave_find_row(rowptr, M, tr.first * (unsigned)T, lane);
-    unsigned rs_lo = (unsigned)rowptr[r_lo];
+    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);
+    unsigned js = mr.d0 - (unsigned)is;
 
-    for (unsigned tile = tr.first; tile < tr.last; ++tile) {
-        const unsigned ts = tile * (unsigned)T;
-        const unsigned te = (nnz - ts > (unsigned)T) ? ts + T : nnz;
+    for (unsigned ds = mr.d0; ds < mr.d1; ds += W) {
+        const unsigned de = (mr.d1 - ds > (unsigned)W) ? ds + W : mr.d1;
 
         wave_lds_sync();                        // previous tile's readers are done
+        // entries: at most W, the exact count follows from the row ends
 #pragma unroll
-        for (int j = 0; j < T / kWave; ++j) {
-            const int e = j * kWave + lane;
-            const unsigned p = ts + (unsigned)e;
-            if (p < te) { cc[e] = stream_load(colidx + p); cv[e] = stream_load(vals + p); }
+        for (int k = 0; k < W / kWave; ++k) {
+            const int e = k * kWave + lane;
+            const unsigned p = js + (unsigned)e;
+            if (p < nnz) { cc[e] = stream_load(colidx + p); cv[e] = stream_load(vals + p); }
         }
-        const RowWindow w = build_row_window<T>(rowptr, M, win, r_lo, rs_lo, te, lane);   // syncs LDS
+        // end offsets of rows is, is+1, ... while their end marker is inside the tile
+        int ie = is;
+        for (int m = 0; m < W / kWave; ++m) {
+            const long long r = (long long)is + m * kWave + lane;
+            bool in = false;
+            if (r < M) {
+                const unsigned e = (unsigned)rowptr[r + 1];
+                in = (unsigned)r + e < de;
+                if (in) ends[m * kWave + lane] = e;
+            }
+            const int cnt = __popcll(__ballot(in));
+            ie += cnt;
+            if (cnt < kWave) break;
+        }
+        const int nrows = ie - is;              // rows ending in this tile
+        const unsigned rs_first = is < M ? (unsigned)rowptr[is] : nnz;   // start offset of row `is`
+        wave_lds_sync();
 
-        const unsigned run_lo = ts + ((unsigned)g << logU);
-        if (run_lo < te && col_ok) {
-            const unsigned run_hi = (te - run_lo > U) ? run_lo + U : te;
-            int cnt; unsigned rs, next;
-            w.locate(run_lo, cnt, rs, next);     // row r_lo+cnt spans [rs, next)
+        const unsigned dg = ds + ((unsigned)g << logU);   // my run: diagonals [dg, dh)
+        if (dg < de && col_ok) {
+            const unsigned dh = (de - dg > U) ? dg + U : de;
+            // rows (local index t, row is+t) whose end marker lies before a diagonal d: is+t + ends[t] < d
+            auto rows_before = [&](unsigned d) {
+                int lo = 0, hi = nrows;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if ((unsigned)(is + mid) + ends[mid] < d) lo = mid + 1; else hi = mid;
+                }
+                return lo;
+            };
+            int t = rows_before(dg);                         // first row (local) to end at or after dg
+            const int t_end = rows_before(dh);               // rows [t, t_end) end inside my run
+            unsigned j = dg - (unsigned)(is + t);            // first entry of my run
+            const unsigned j_end = dh - (unsigned)(is + t_end);
+            unsigned next_end = t < nrows ? ends[t] : kNoRow;   // end offset of the current row
+            // the current row's first item lies before my run?  (its start offset is the previous row's end)
+            const unsigned cur_start = t == 0 ? rs_first : ends[t - 1];
+            bool split = (unsigned)(is + t) + cur_start < dg;
+
             float acc[V];
 #pragma unroll
             for (int i = 0; i < V; ++i) acc[i] = 0.0f;
 
-            for (unsigned p0 = run_lo; p0 < run_hi; p0 += 4) {
+            auto flush_rows_ending_at = [&](unsigned pos) {
+                while (next_end == pos && t < t_end) {
+                    float* y = Y + (size_t)((long long)is + t) * N + n;
+                    if (split) atomic_add_vec<V>(y, acc); else store_vec<V>(y, acc);
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+                    split = false;
+                    ++t;
+                    next_end = t < nrows ? ends[t] : kNoRow;
+                }
+            };
+
+            for (unsigned p0 = j; p0 < j_end; p0 += 4) {
                 float x[4][V]; float a[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const unsigned p = p0 + u;
-                    if (p < run_hi) {
-                        const int e = (int)(p - ts);
+                    if (p < j_end) {
+                        const int e = (int)(p - js);
                         a[u] = cv[e];
                         load_vec<V>(X + (size_t)cc[e] * N + n, x[u]);
                     } else {
@@ -413,28 +580,23 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const unsigned p = p0 + u;
-                    if (p < run_hi) {
-                        if (p == next) {
-                            // row r_lo+cnt is complete as far as this run goes
-                            float* y = Y + (size_t)((long long)r_lo + cnt) * N + n;
-                            if (rs < run_lo) atomic_add_vec<V>(y, acc); else store_vec<V>(y, acc);
-#pragma unroll
-                            for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-                            do { ++cnt; rs = next; next = w.entry(cnt); } while (next <= p);   // skips empty rows
-                        }
+                    if (p < j_end) {
+                        flush_rows_ending_at(p);             // rows that end before entry p
 #pragma unroll
                         for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);
                     }
                 }
             }
-            float* y = Y + (size_t)((long long)r_lo + cnt) * N + n;
-            if (rs < run_lo || next > run_hi) atomic_add_vec<V>(y, acc); else store_vec<V>(y, acc);
+            flush_rows_ending_at(j_end);                     // rows whose end marker closes my run
+            // what is left belongs to a row that ends in a later run
+            bool any = false;
+#pragma unroll
+            for (int i = 0; i < V; ++i) any |= acc[i] != 0.0f;
+            if (any) atomic_add_vec<V>(Y + (size_t)((long long)is + t) * N + n, acc);
         }
 
-        int lc; unsigned lrs, lre;
-        w.locate(te - 1, lc, lrs, lre);
-        r_lo = uniform(r_lo + lc);
-        rs_lo = (unsigned)uniform((int)lrs);
+        js = de - (unsigned)ie;
+        is = ie;
     }
 }
 
