@@ -6,7 +6,9 @@
 
 #include <cmath>
 #include <cstdint>
+#include <map>
 #include <mutex>
+#include <utility>
 
 #include "dgsp_kernels.hpp"
 
@@ -116,32 +118,51 @@ int launch_rs_sr(const Problem& p) {
 }
 
 // ---------------------------------------------------------------- balanced launches
-// `unit` > 0: rows split by a multiple of `unit` merge-path items are zeroed;
-// unit == 0: the unit is the per-wave share of tiles of W items on nwaves waves.
-int launch_prepare(const Problem& p, unsigned unit, unsigned W, unsigned nwaves) {
+// Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: the chunk size the
+// main kernel derives for `parts` chunks rounded to `quantum` items.
+int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum) {
     int logP = ilog2_ceil(p.N);
     if (logP > 6) logP = 6;
     const long long threads = (long long)p.M << logP;
     const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, W, nwaves, logP);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, logP);
     return DGSP_OK;
 }
 
-// blocks of a machine-filling grid whose waves share nnz + M merge-path items in tiles of `tile`
-inline unsigned balanced_blocks(const Problem& p, int tile) {
-    const long long cap = (long long)device_info().cus * kBlocksPerCu;
+// Workgroups of `kernel` that one CU keeps resident (registers and LDS decide).  The balanced
+// kernels cut the work into equal shares per wave, so their grid must not exceed what runs at
+// once: a workgroup that waits for a slot would start its share when the others are done.
+template <typename K>
+int resident_blocks_per_cu(K kernel) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, int> cache;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 4;
+    const auto key = std::make_pair(reinterpret_cast<const void*>(kernel), dev);
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n <= 0) n = 4;
+    cache[key] = n;
+    return n;
+}
+
+// blocks of a machine-filling grid that shares nnz + M merge-path items in chunks of `chunk`
+inline unsigned balanced_blocks(const Problem& p, long long chunk, int blocks_per_cu) {
+    const long long cap = (long long)device_info().cus * blocks_per_cu;
     if (p.nnz < 0) return (unsigned)cap;
-    const long long tiles = (p.nnz + p.M + tile - 1) / tile;
-    return clamp_blocks((tiles + kWavesPerBlock - 1) / kWavesPerBlock, cap);
+    const long long chunks = (p.nnz + p.M + chunk - 1) / chunk;
+    return clamp_blocks((chunks + kWavesPerBlock - 1) / kWavesPerBlock, cap);
 }
 
 template <int V, int KQ>
 int launch_nb_pr_v(const Problem& p) {
-    constexpr int W = kWave * 4 * KQ;
+    constexpr unsigned tile = kWave * 4 * KQ;
     const unsigned col_groups = (unsigned)(p.N / V);
     if (col_groups > 65535u) return DGSP_ERR_INVALID_ARG;
-    const dim3 grid(balanced_blocks(p, W), col_groups);
-    if (int rc = launch_prepare(p, 0, W, grid.x * kWavesPerBlock)) return rc;
+    const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>)), col_groups);
+    if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave)) return rc;
     DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
 }
@@ -154,21 +175,25 @@ int launch_nb_pr(const Problem& p) {
     }
 }
 
-int launch_nb_sr(const Problem& p) {
-    const int V = vector_width(p.N, p.X, p.Y);
+template <int V>
+int launch_nb_sr_v(const Problem& p) {
     const int logG = sr_lanes_log2(p.N, V);
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
+    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V>)), col_blocks);
     if (int rc = launch_prepare(p, 1u << logU, 0, 0)) return rc;
-    const dim3 grid(balanced_blocks(p, kNbSrTile), col_blocks);
-    switch (V) {
-        case 4: DGSP_LAUNCH(nb_sr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        case 2: DGSP_LAUNCH(nb_sr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        default: DGSP_LAUNCH(nb_sr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-    }
+    DGSP_LAUNCH(nb_sr_kernel<V>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
+}
+
+int launch_nb_sr(const Problem& p) {
+    switch (vector_width(p.N, p.X, p.Y)) {
+        case 4: return launch_nb_sr_v<4>(p);
+        case 2: return launch_nb_sr_v<2>(p);
+        default: return launch_nb_sr_v<1>(p);
+    }
 }
 
 // ---------------------------------------------------------------- selector state

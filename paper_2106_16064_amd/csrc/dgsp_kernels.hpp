@@ -191,36 +191,68 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
 // of a piece.  For matrices without empty stretches it is the paper's fixed
 // share of non-zeros up to the few percent that row markers add.
 //
-// Tiles of W items are dealt to the waves in contiguous ranges (XCD-contiguous
-// again); a wave finds its first row once with a 64-way search and then walks.
+// The list is cut into kSubRanges * (number of resident waves) contiguous
+// chunks; wave w takes chunks w, w + nwaves, ... (waves of one XCD hold
+// neighbouring chunks).  Equal shares do not take equal time - the dense-matrix
+// gather of one region hits in cache, that of another does not - and dealing
+// each wave chunks from far-apart regions evens that out without any shared
+// counter (one contended atomic costs more than a tile on this machine).  A
+// wave finds the first row of a chunk with a 64-way search and then walks.
 //
-// Rows whose items straddle a partition boundary are combined with fp32
-// atomic adds (the paper does not say how partial rows of different warps
-// meet), which needs zeros underneath.  A small "prepare" kernel zeroes
-// exactly those rows and no others; every other row, empty ones included, is
-// written once with a plain store by the tile that holds its end marker.
+// Rows whose items straddle a chunk boundary (in the sequential kernel: the
+// boundary of a lane group's run) are combined with fp32 atomic adds; the
+// paper does not say how partial rows of different warps meet.  That needs
+// zeros underneath.  A small "prepare" kernel zeroes exactly those rows and no
+// others; every other row, empty ones included, is written once with a plain
+// store by the chunk that holds its end marker.
 
-__device__ __forceinline__ unsigned merge_items_per_wave(unsigned items, unsigned W, unsigned nwaves) {
-    const unsigned ntiles = items / W + (items % W != 0);
-    const unsigned tpw = ntiles / nwaves + (ntiles % nwaves != 0);
-    return tpw * W;
+constexpr unsigned kSubRanges = 1;
+
+// Items per chunk when `items` merge-path items are shared by `parts` chunks,
+// rounded up to a multiple of `quantum`.
+__device__ __forceinline__ unsigned merge_chunk_items(unsigned items, unsigned parts, unsigned quantum) {
+    unsigned per = items / parts + (items % parts != 0);
+    per = ((per + quantum - 1) / quantum) * quantum;
+    return per ? per : quantum;
 }
 
-// Zeroes the rows that are split by a multiple of `unit` items.  unit == 0
-// means "derive it from the wave partition" (items per wave for tiles of W
-// items on nwaves waves).  2^logP consecutive threads share a row.
+// Zeroes the rows that are split by a multiple of `unit` items.  unit == 0:
+// the unit is the chunk size for `parts` chunks (see merge_chunk_items).
+// 2^logP consecutive threads share a row.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
-                                                             float* __restrict__ Y, unsigned unit, unsigned W,
-                                                             unsigned nwaves, int logP) {
+                                                             float* __restrict__ Y, unsigned unit, unsigned parts,
+                                                             unsigned quantum, int logP) {
     const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
     const long long row = t >> logP;
     if (row >= M) return;
-    if (unit == 0) unit = merge_items_per_wave((unsigned)rowptr[M] + (unsigned)M, W, nwaves);
+    if (unit == 0) unit = merge_chunk_items((unsigned)rowptr[M] + (unsigned)M, parts, quantum);
     const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
     const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
     if (first / unit == last / unit) return;
     float* y = Y + (size_t)row * N;
     for (int n = (int)(t & ((1 << logP) - 1)); n < N; n += 1 << logP) y[n] = 0.0f;
+}
+
+// The chunks of the calling wave: chunk(s) = s * nwaves + wave id, s < kSubRanges.
+struct ChunkPlan {
+    unsigned nnz, items, per, nwaves, gw;
+    __device__ __forceinline__ bool range(unsigned s, unsigned& d0, unsigned& d1) const {
+        const unsigned long long a = (unsigned long long)(s * nwaves + gw) * per;
+        if (a >= items) return false;
+        d0 = (unsigned)a;
+        d1 = items - d0 > per ? d0 + per : items;
+        return true;
+    }
+};
+
+__device__ __forceinline__ ChunkPlan plan_chunks(const int* __restrict__ rowptr, int M, unsigned quantum) {
+    ChunkPlan p;
+    p.nnz = (unsigned)rowptr[M];
+    p.items = p.nnz + (unsigned)M;
+    p.nwaves = gridDim.x * kWavesPerBlock;
+    p.gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
+    p.per = merge_chunk_items(p.items, p.nwaves * kSubRanges, quantum);
+    return p;
 }
 
 // Number of rows whose end marker lies before diagonal d, i.e. rows r with
@@ -247,47 +279,33 @@ __device__ __forceinline__ int wave_merge_rows_before(const int* __restrict__ ro
     return uniform(lo);
 }
 
-struct MergeRange {
-    unsigned nnz, items;
-    unsigned d0, d1;      // my diagonals [d0, d1)
-};
-
-template <int W>
-__device__ __forceinline__ MergeRange my_merge_range(const int* __restrict__ rowptr, int M) {
-    MergeRange r;
-    r.nnz = (unsigned)rowptr[M];
-    r.items = r.nnz + (unsigned)M;
-    const unsigned nwaves = gridDim.x * kWavesPerBlock;
-    const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
-    const unsigned per = merge_items_per_wave(r.items, W, nwaves);
-    const unsigned long long a = (unsigned long long)gw * per;
-    r.d0 = a < r.items ? (unsigned)a : r.items;
-    r.d1 = a + per < r.items ? (unsigned)(a + per) : r.items;
-    return r;
-}
-
 constexpr unsigned kNoRow = 0xffffffffu;
-
-typedef int int4u __attribute__((ext_vector_type(4), aligned(4)));       // dwordx4 at dword alignment
-typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
 
 // ===========================================================================
 // nnz-balanced, parallel reduction: vectorized segment reduction (Section 2.1.1)
 // ===========================================================================
 //
-// Tile = W = 64*E items, E = 4*KQ.  Lane l owns the E consecutive entries
-// js + E*l ... of the tile (one or two dwordx4 loads per array), gathers V
-// dense values per entry, multiplies, and first reduces its own entries in
-// order.  Row ends are scattered into LDS as "row i ends after entry q"
-// marks, so a lane sees its boundaries with one 16-byte LDS read.  A lane
-// without a boundary contributes its whole sum to the row that is open
-// across lanes; a lane with boundaries closes that open row with its leading
-// part, stores the rows that lie inside it, and opens a new segment with its
-// trailing part.  The open row's running sum across lanes is the paper's
-// segment reduction: the wave64 DPP scan whose operator is "add unless a row
-// boundary lies in between".  The sum that is still open at the end of a
-// tile is handed to the wave's next tile in a register; only the two ends
-// of a wave's range can need an atomic add.
+// Tile = W = 64*E items (E = 4*KQ entries per lane).
+//   1. Entry 64*e + l of the tile is loaded by lane l (coalesced dword loads),
+//      which gathers V dense values for it with one vector load and
+//      multiplies.  Consecutive lanes hold consecutive entries, so the gather
+//      of a wave touches as few cache lines as the matrix allows.
+//   2. The products go through LDS once to change hands: afterwards lane l
+//      holds the products of the E consecutive entries E*l ... and reduces them
+//      in order in registers.
+//   3. Row ends are scattered into LDS as "row i ends after entry q" marks, so
+//      a lane sees its own boundaries with one 16-byte LDS read.  A lane
+//      without a boundary contributes its whole sum to the row that is open
+//      across lanes; a lane with boundaries closes that open row with its
+//      leading part, stores the rows that lie inside it, and opens a new
+//      segment with its trailing part.
+//   4. The open row's running sum across lanes is the paper's segment
+//      reduction: the wave64 DPP scan whose operator is "add unless a row
+//      boundary lies in between" (one scan per tile instead of one per 64
+//      entries).  The lanes that hold a boundary "dump" the finished rows.
+//   5. The sum still open at the end of a tile is handed to the chunk's next
+//      tile in a register; only the two ends of a chunk can need an atomic add.
+// The loads of the next tile are issued before the current tile is reduced.
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
 template <int V, int KQ>
@@ -298,17 +316,22 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
     constexpr int E = 4 * KQ;
     constexpr int W = kWave * E;
     __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W] = "ends before the tile's first entry"
+    __shared__ float s_prod[kWavesPerBlock][W * V];
     const int lane = lane_id();
-    unsigned* bnd = s_bnd[wave_in_block()];
+    const int wib = wave_in_block();
+    unsigned* bnd = s_bnd[wib];
+    float* prod = s_prod[wib];
     const int n0 = blockIdx.y * V;
+    const ChunkPlan plan = plan_chunks(rowptr, M, kWave);
+    const unsigned nnz = plan.nnz;
 
-    const MergeRange mr = my_merge_range<W>(rowptr, M);
-    if (mr.d0 >= mr.d1) return;
-    const unsigned nnz = mr.nnz;
+    for (unsigned sub = 0; sub < kSubRanges; ++sub) {
+    struct { unsigned d0, d1; } mr;
+    if (!plan.range(sub, mr.d0, mr.d1)) break;
 
-    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);   // rows that ended before my range
-    unsigned js = mr.d0 - (unsigned)is;                        // entries consumed before my range
-    // the first row to end in my range started before it?  then its sum is shared with another wave
+    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);   // rows that ended before my chunk
+    unsigned js = mr.d0 - (unsigned)is;                        // entries consumed before my chunk
+    // the first row to end in my chunk started before it?  then its sum is shared with another wave
     const int r_first = is;
     const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < mr.d0;
 
@@ -316,33 +339,33 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
         float* y = Y + (size_t)row * N + n0;
         if (first_split && row == r_first) atomic_add_vec<V>(y, val); else store_vec<V>(y, val);
     };
+    // entries of a tile starting at entry `from`: at most W, the real count is known later
+    auto load_entries = [&](unsigned from, int (&c)[E], float (&a)[E]) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const unsigned p = from + (unsigned)(e * kWave + lane);
+            const bool ok = p < nnz;
+            c[e] = ok ? stream_load(colidx + p) : 0;
+            a[e] = ok ? stream_load(vals + p) : 0.0f;
+        }
+    };
+    // start and end offset of row `first + lane` (the first 64 candidates for "ends in the tile")
+    auto load_row_bounds = [&](int first, unsigned& start, unsigned& end) {
+        const long long r = (long long)first + lane;
+        start = 0; end = 0;
+        if (r < M) { start = (unsigned)rowptr[r]; end = (unsigned)rowptr[r + 1]; }
+    };
 
     float carry[V];      // running sum of the row that is open at the tile boundary (wave-uniform)
 #pragma unroll
     for (int i = 0; i < V; ++i) carry[i] = 0.0f;
 
+    int c[E]; float a[E]; unsigned w_start, w_end;
+    load_entries(js, c, a);
+    load_row_bounds(is, w_start, w_end);
+
     for (unsigned ds = mr.d0; ds < mr.d1; ds += W) {
         const unsigned de = (mr.d1 - ds > (unsigned)W) ? ds + W : mr.d1;
-
-        // ---- sparse entries (at most W of them; the tile's real count is known later)
-        int c[E]; float a[E];
-#pragma unroll
-        for (int k = 0; k < KQ; ++k) {
-            const unsigned p = js + (unsigned)(E * lane + 4 * k);
-            if (p + 4 <= nnz) {
-                const int4u cv = __builtin_nontemporal_load(reinterpret_cast<const int4u*>(colidx + p));
-                const float4u av = __builtin_nontemporal_load(reinterpret_cast<const float4u*>(vals + p));
-                c[4 * k] = cv.x; c[4 * k + 1] = cv.y; c[4 * k + 2] = cv.z; c[4 * k + 3] = cv.w;
-                a[4 * k] = av.x; a[4 * k + 1] = av.y; a[4 * k + 2] = av.z; a[4 * k + 3] = av.w;
-            } else {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const bool ok = p + u < nnz;
-                    c[4 * k + u] = ok ? colidx[p + u] : 0;
-                    a[4 * k + u] = ok ? vals[p + u] : 0.0f;
-                }
-            }
-        }
 
         // ---- row ends of this tile -> LDS marks
         wave_lds_sync();                                   // the previous tile's readers are done
@@ -352,31 +375,56 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
         if (lane == 0) bnd[W] = kNoRow;
         wave_lds_sync();
         int ie = is;
-        for (int m = 0; m < E; ++m) {                      // a tile holds at most W row ends
+        // marks the rows of one batch of 64 candidates that end in the tile; returns how many did
+        auto mark_row_ends = [&](int m, unsigned start, unsigned end) {
             const long long r = (long long)is + m * kWave + lane;
-            bool ends = false;
-            if (r < M) {
-                const unsigned e = (unsigned)rowptr[r + 1];
-                ends = (unsigned)r + e < de;               // the row's end marker is inside the tile
-                if (ends) {
-                    const unsigned q = e - js;             // it ends after entry q-1 of the tile
-                    atomicMin(bnd + (q ? q - 1 : (unsigned)W), (unsigned)(r - is));
-                    // empty rows other than the tile's first get their zeros here: no sum ever closes them
-                    if (r > is && (unsigned)rowptr[r] == e) {
-                        float zero[V];
+            const bool ends = r < M && (unsigned)r + end < de;     // the row's end marker is inside the tile
+            if (ends) {
+                const unsigned q = end - js;               // it ends after entry q-1 of the tile
+                atomicMin(bnd + (q ? q - 1 : (unsigned)W), (unsigned)(r - is));
+                // empty rows other than the tile's first get their zeros here: no sum ever closes them
+                if (r > is && start == end) {
+                    float zero[V];
 #pragma unroll
-                        for (int i = 0; i < V; ++i) zero[i] = 0.0f;
-                        store_vec<V>(Y + (size_t)r * N + n0, zero);
-                    }
+                    for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+                    store_vec<V>(Y + (size_t)r * N + n0, zero);
                 }
             }
-            const int cnt = __popcll(__ballot(ends));
-            ie += cnt;
-            if (cnt < kWave) break;
+            return (int)__popcll(__ballot(ends));
+        };
+        int cnt = mark_row_ends(0, w_start, w_end);        // the first 64 candidates were loaded a tile ago
+        ie += cnt;
+        if (cnt == kWave) {
+            // a tile crowded with row ends (at most W of them): fetch all remaining candidates at once
+            unsigned ms[E - 1], me[E - 1];
+#pragma unroll
+            for (int m = 1; m < E; ++m) load_row_bounds(is + m * kWave, ms[m - 1], me[m - 1]);
+#pragma unroll
+            for (int m = 1; m < E; ++m) {
+                if (cnt == kWave) { cnt = mark_row_ends(m, ms[m - 1], me[m - 1]); ie += cnt; }
+            }
         }
         const unsigned je = de - (unsigned)ie;             // entries [js, je) belong to the tile
         const int nE = (int)(je - js);
         wave_lds_sync();
+
+        // ---- gather for this tile, then the next tile's loads (they stay in flight during the reduction)
+        float x[E][V];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (e * kWave + lane < nE) load_vec<V>(X + (size_t)c[e] * N + n0, x[e]);
+            else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) x[e][i] = 0.0f;
+                a[e] = 0.0f;
+            }
+        }
+        int c2[E]; float a2[E]; unsigned w_start2 = 0, w_end2 = 0;
+        const bool more = mr.d1 - ds > (unsigned)W;
+        if (more) {
+            load_entries(je, c2, a2);
+            load_row_bounds(ie, w_start2, w_end2);
+        }
 
         // ---- rows that end before the tile's first entry take the sum carried in
         const unsigned b_in = bnd[W];
@@ -386,23 +434,26 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
             for (int i = 0; i < V; ++i) carry[i] = 0.0f;
         }
 
-        // ---- my boundaries, gather, products, in-lane reduction
+        // ---- products change hands through LDS: entry 64e+l -> lane (64e+l)/E
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float p[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) p[i] = a[e] * x[e][i];
+            store_vec<V>(prod + (size_t)(e * kWave + lane) * V, p);
+        }
+        wave_lds_sync();
         unsigned b[E];
 #pragma unroll
         for (int k = 0; k < KQ; ++k) {
             const uint4 t = *reinterpret_cast<const uint4*>(bnd + E * lane + 4 * k);
             b[4 * k] = t.x; b[4 * k + 1] = t.y; b[4 * k + 2] = t.z; b[4 * k + 3] = t.w;
         }
-        float x[E][V];
+        float pr[E][V];
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            if (E * lane + e < nE) load_vec<V>(X + (size_t)c[e] * N + n0, x[e]);
-            else {
-#pragma unroll
-                for (int i = 0; i < V; ++i) x[e][i] = 0.0f;
-                a[e] = 0.0f;
-            }
-        }
+        for (int e = 0; e < E; ++e) load_vec<V>(prod + (size_t)(E * lane + e) * V, pr[e]);
+
+        // ---- in-lane reduction over my E consecutive entries
         float s[V], head[V];
         unsigned head_row = kNoRow;                        // kNoRow: no boundary inside this lane
 #pragma unroll
@@ -410,7 +461,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
 #pragma unroll
         for (int e = 0; e < E; ++e) {
 #pragma unroll
-            for (int i = 0; i < V; ++i) s[i] = fmaf(a[e], x[e][i], s[i]);
+            for (int i = 0; i < V; ++i) s[i] += pr[e][i];
             if (b[e] != kNoRow) {
                 if (head_row == kNoRow) {
                     head_row = b[e];
@@ -439,13 +490,19 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
 
         is = ie;
         js = je;
+        if (more) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) { c[e] = c2[e]; a[e] = a2[e]; }
+            w_start = w_start2; w_end = w_end2;
+        }
     }
 
-    // the row still open at the end of my range is finished by another wave
+    // the row still open at the end of my chunk is finished by another wave
     bool any = false;
 #pragma unroll
     for (int i = 0; i < V; ++i) any |= carry[i] != 0.0f;
     if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * N + n0, carry);
+    }   // next chunk
 }
 
 // ===========================================================================
@@ -489,15 +546,16 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
     const long long n = ((long long)blockIdx.y * G + gl) * V;
     const bool col_ok = n < N;
 
-    const MergeRange mr = my_merge_range<W>(rowptr, M);
-    if (mr.d0 >= mr.d1) return;
-    const unsigned nnz = mr.nnz;
+    const ChunkPlan plan = plan_chunks(rowptr, M, W);     // chunks are whole tiles: runs stay aligned to U
+    const unsigned nnz = plan.nnz;
 
-    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);
-    unsigned js = mr.d0 - (unsigned)is;
-
-    for (unsigned ds = mr.d0; ds < mr.d1; ds += W) {
-        const unsigned de = (mr.d1 - ds > (unsigned)W) ? ds + W : mr.d1;
+    for (unsigned sub = 0; sub < kSubRanges; ++sub) {
+    unsigned d0, d1;
+    if (!plan.range(sub, d0, d1)) break;
+    int is = wave_merge_rows_before(rowptr, M, d0, lane);
+    unsigned js = d0 - (unsigned)is;
+    for (unsigned ds = d0; ds < d1; ds += W) {
+        const unsigned de = (d1 - ds > (unsigned)W) ? ds + W : d1;
 
         wave_lds_sync();                        // previous tile's readers are done
         // entries: at most W, the exact count follows from the row ends
@@ -598,6 +656,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
         js = de - (unsigned)ie;
         is = ie;
     }
+    }   // next chunk
 }
 
 // ===========================================================================
