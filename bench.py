@@ -95,6 +95,14 @@ class Rotation:
         j = 0 if warm else i % self.copies
         self.mats[j].spmm(self.X[j], algo=algo, Y=self.Y[j])
 
+    def phase(self, i, algo, phase):
+        """One launch of a call (measurement aid): the prepare step or the main kernel alone."""
+        from paper_2106_16064_amd import binding as dg
+        j = i % self.copies
+        m = self.mats[j]
+        dg.dgsp_spmm_csr_phase(m.M, m.K, self.N, m.nnz, m.rowptr, m.colidx, m.vals, self.X[j], self.Y[j],
+                               algo, phase)
+
 
 def time_steps(rot, algo, steps, warmup, warm=False):
     """Wall-clock ms per step over `steps` back-to-back launches."""
@@ -145,6 +153,18 @@ def copy_bandwidth(nbytes=1 << 30, reps=10):
     return 2 * nbytes / (median(ms) * 1e-3) / 1e9
 
 
+def gather_floor(rot):
+    """Time (ms) of the pure-gather probe on this matrix's column indices with N = 1: what
+    the machine needs just to stream colidx and fetch one dense value per stored entry."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    out = torch.empty(dg.dgsp_gather_probe_out_len(), dtype=torch.float32, device="cuda:0")
+    xs = [torch.zeros(rot.A.K, dtype=torch.float32, device="cuda:0") for _ in range(rot.copies)]
+    ms = time_events(None, lambda i: dg.dgsp_gather_probe(out, xs[i % rot.copies], rot.mats[i % rot.copies].colidx),
+                     20, 3)
+    return median(ms)
+
+
 def cpu_baseline(A, X, budget_s=8.0):
     """The CPU oracle (test infrastructure, never tuned) on the same workload."""
     import oracle
@@ -188,9 +208,12 @@ def run_headline(args):
     ms_cold = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=False)
     ms_warm = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=True)
 
-    # dominant kernel alone: for the balanced kernels the small prepare launch runs untimed first
-    ev = time_events(None, lambda i: rot.step(i, chosen), args.steps, args.warmup)
+    # dominant kernel alone: the small prepare launch of the balanced kernels runs untimed first
+    ev = time_events(lambda i: rot.phase(i, chosen, dg.PHASE_PREPARE), lambda i: rot.phase(i, chosen, dg.PHASE_MAIN),
+                     args.steps, args.warmup)
     ev_ms = sum(ev) / len(ev)
+    kernel_name = {0: "rs_sr_kernel", 1: "rs_pr_kernel", 2: "nb_sr_kernel", 3: "nb_pr_kernel"}[chosen]
+    floor_ms = gather_floor(rot) if N == 1 else None
 
     bytes_alg = algorithmic_bytes(A, N)
     flops = 2.0 * A.nnz * N
@@ -223,8 +246,9 @@ def run_headline(args):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(f"{sel_name}/{args.workload or 'rmat_spmv'}/N{N}"),
-                     "kernel": f"{sel_name} (whole call, HIP events, mean of {len(ev)} launches)",
-                     "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms},
+                     "kernel": f"dgsp::{kernel_name} (main launch alone, HIP events, mean of {len(ev)} launches)",
+                     "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms,
+                     "gather_probe_ms": floor_ms},
         "cpu_baseline": cpu_baseline(A, X),
     }
     print(json.dumps(out))

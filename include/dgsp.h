@@ -156,6 +156,37 @@ int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t *rowptr_h
                                    dgsp_features_t *out);
 
 /*
+ * Measurement aid: the same multiplication, one step at a time.  The two
+ * nnz-balanced kernels are two launches per call - a small "prepare" launch
+ * (zeroes the rows that are later combined with atomic adds) and the main
+ * kernel.  A profiler sees them apart; a benchmark that brackets launches with
+ * events needs this entry to time the main kernel alone.
+ *   phase = DGSP_PHASE_ALL      same as dgsp_spmm_csr_nnz
+ *           DGSP_PHASE_PREPARE  only the prepare launch (no-op for row-split algos)
+ *           DGSP_PHASE_MAIN     only the main kernel; the result is right only if
+ *                               PREPARE for the same arguments ran before it on
+ *                               the same stream
+ * algo must be one of the four kernels (not DGSP_AUTO).
+ */
+typedef enum { DGSP_PHASE_ALL = 0, DGSP_PHASE_PREPARE = 1, DGSP_PHASE_MAIN = 2 } dgsp_phase_t;
+int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                        const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *X, float *Y, int algo, int phase, void *stream);
+
+/*
+ * Measurement aid, not part of the method: out[t] = sum of x[idx[i]] over the
+ * i that thread t visits (device buffers; idx int32[n] with 0 <= idx[i] < the
+ * length of x; out fp32[dgsp_gather_probe_out_len()]).  It does nothing but
+ * stream idx and gather from x, so its time is a floor for any kernel that
+ * has to gather one dense value per stored entry (Section 2.1.2 names the
+ * scattered dense-vector reads as the cost of parallel-reduction SpMV): run on
+ * a matrix's colidx it gives the rate at which this machine can serve that
+ * matrix's access pattern at all.
+ */
+int dgsp_gather_probe(float *out, const float *x, const int32_t *idx, int64_t n, void *stream);
+int64_t dgsp_gather_probe_out_len(void);
+
+/*
  * Measurement aid, not part of the method: dst[i] = src[i] for i < n (device
  * fp32 buffers, n >= 0), a plain streaming copy whose 8*n bytes calibrate the
  * achievable HBM bandwidth and the profiler's byte counters.

@@ -21,7 +21,9 @@ EXPORTS = (
     "dgsp_spmm_csr", "dgsp_spmm_csr_nnz", "dgsp_spmm_csr_auto", "dgsp_select_algo",
     "dgsp_get_thresholds", "dgsp_set_thresholds", "dgsp_features_from_rowptr_host",
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
+    "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len",
 )
+PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 
 
 class Features(ctypes.Structure):
@@ -72,6 +74,12 @@ def lib():
         L.dgsp_set_thresholds.argtypes = [ctypes.POINTER(Thresholds)]
         L.dgsp_features_from_rowptr_host.restype = ci
         L.dgsp_features_from_rowptr_host.argtypes = [i64, i64, vp, ctypes.POINTER(Features)]
+        L.dgsp_spmm_csr_phase.restype = ci
+        L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, vp]
+        L.dgsp_gather_probe.restype = ci
+        L.dgsp_gather_probe.argtypes = [vp, vp, vp, i64, vp]
+        L.dgsp_gather_probe_out_len.restype = i64
+        L.dgsp_gather_probe_out_len.argtypes = []
         L.dgsp_copy_f32.restype = ci
         L.dgsp_copy_f32.argtypes = [vp, vp, i64, vp]
         L.dgsp_algo_name.restype = ctypes.c_char_p
@@ -126,6 +134,27 @@ def dgsp_spmm_csr_nnz(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, stream=Non
     rc = lib().dgsp_spmm_csr_nnz(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
                                  int(algo), _stream(stream))
     _check(rc, "dgsp_spmm_csr_nnz")
+
+
+def dgsp_spmm_csr_phase(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, phase, stream=None):
+    """One step of the multiplication (measurement aid): PHASE_PREPARE, PHASE_MAIN or PHASE_ALL."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    rc = lib().dgsp_spmm_csr_phase(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
+                                   int(algo), int(phase), _stream(stream))
+    _check(rc, "dgsp_spmm_csr_phase")
+
+
+def dgsp_gather_probe(out, x, idx, n=None, stream=None):
+    """``out[t] = sum x[idx[i]]`` (measurement aid: the pure gather rate of an index pattern)."""
+    n = idx.numel() if n is None else n
+    if out.numel() < dgsp_gather_probe_out_len():
+        raise DgspError("out is shorter than dgsp_gather_probe_out_len()")
+    rc = lib().dgsp_gather_probe(_ptr(out), _ptr(x), _ptr(idx), int(n), _stream(stream))
+    _check(rc, "dgsp_gather_probe")
+
+
+def dgsp_gather_probe_out_len() -> int:
+    return int(lib().dgsp_gather_probe_out_len())
 
 
 def dgsp_spmm_csr_auto(M, K, N, features: Features, rowptr, colidx, vals, X, Y, stream=None) -> int:

@@ -66,6 +66,7 @@ struct Problem {
     long long K, nnz;   // nnz < 0: unknown on the host
     const int* rowptr; const int* colidx; const float* vals; const float* X; float* Y;
     hipStream_t stream;
+    int phase = DGSP_PHASE_ALL;
 };
 
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
@@ -162,8 +163,10 @@ int launch_nb_pr_v(const Problem& p) {
     const unsigned col_groups = (unsigned)(p.N / V);
     if (col_groups > 65535u) return DGSP_ERR_INVALID_ARG;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>)), col_groups);
-    if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave)) return rc;
-    DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+    if (p.phase != DGSP_PHASE_MAIN)
+        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave)) return rc;
+    if (p.phase != DGSP_PHASE_PREPARE)
+        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
 }
 
@@ -183,8 +186,10 @@ int launch_nb_sr_v(const Problem& p) {
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V>)), col_blocks);
-    if (int rc = launch_prepare(p, 1u << logU, 0, 0)) return rc;
-    DGSP_LAUNCH(nb_sr_kernel<V>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    if (p.phase != DGSP_PHASE_MAIN)
+        if (int rc = launch_prepare(p, 1u << logU, 0, 0)) return rc;
+    if (p.phase != DGSP_PHASE_PREPARE)
+        DGSP_LAUNCH(nb_sr_kernel<V>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
@@ -207,7 +212,7 @@ dgsp_thresholds_t g_thresholds = {
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
-        const float* vals, const float* X, float* Y, int algo, void* stream) {
+        const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
     if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return DGSP_OK;
@@ -219,10 +224,10 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
 
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
-    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream};
+    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase};
     switch (algo) {
-        case DGSP_RS_SR: return launch_rs_sr(p);
-        case DGSP_RS_PR: return launch_rs_pr(p);
+        case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
+        case DGSP_RS_PR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_pr(p);
         case DGSP_NB_SR: return launch_nb_sr(p);
         default: return launch_nb_pr(p);
     }
@@ -241,6 +246,14 @@ extern "C" int dgsp_spmm_csr_nnz(int64_t M, int64_t K, int64_t N, int64_t nnz, c
                                  const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
                                  void* stream) {
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream);
+}
+
+extern "C" int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                   const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
+                                   int phase, void* stream) {
+    if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
+    if (phase < DGSP_PHASE_ALL || phase > DGSP_PHASE_MAIN) return DGSP_ERR_INVALID_ARG;
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase);
 }
 
 extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_features_t* features,
@@ -302,6 +315,17 @@ extern "C" int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_
     f.cv_row = f.avg_row > 0 ? f.stdv_row / f.avg_row : 0.0;
     *out = f;
     return DGSP_OK;
+}
+
+constexpr int kGatherProbeBlocks = 4096;
+
+extern "C" int64_t dgsp_gather_probe_out_len(void) { return (int64_t)kGatherProbeBlocks * kBlock; }
+
+extern "C" int dgsp_gather_probe(float* out, const float* x, const int32_t* idx, int64_t n, void* stream) {
+    if (n < 0 || !out || (n > 0 && (!x || !idx))) return DGSP_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(gather_probe_kernel, dim3(kGatherProbeBlocks), dim3(kBlock), 0, (hipStream_t)stream, out, x,
+                       idx, (long long)n);
+    return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
 }
 
 extern "C" int dgsp_copy_f32(float* dst, const float* src, int64_t n, void* stream) {

@@ -660,8 +660,28 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
 }
 
 // ===========================================================================
-// measurement aid: plain streaming copy
+// measurement aids: pure gather, plain streaming copy
 // ===========================================================================
+
+// Streams idx and gathers x[idx[i]], four independent gathers in flight per
+// lane; nothing else.  One partial sum per thread keeps the loads alive.
+__global__ __launch_bounds__(kBlock) void gather_probe_kernel(float* __restrict__ out, const float* __restrict__ x,
+                                                               const int* __restrict__ idx, long long n) {
+    const long long nthreads = (long long)gridDim.x * kBlock;
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+    float acc = 0.0f;
+    for (long long base = t; base < n; base += nthreads * 4) {
+        int c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long long i = base + u * nthreads;
+            c[u] = i < n ? stream_load(idx + i) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc += c[u] >= 0 ? x[c[u]] : 0.0f;
+    }
+    out[t] = acc;
+}
 
 __global__ __launch_bounds__(kBlock) void copy_kernel(float* __restrict__ dst, const float* __restrict__ src,
                                                        long long n) {

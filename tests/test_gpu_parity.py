@@ -268,3 +268,35 @@ def test_copy_kernel(dg):
         dg.dgsp_copy_f32(base[:n], src, n)
         torch.cuda.synchronize()
         assert torch.equal(base[:n], src) and torch.all(base[n:] == 0)
+
+
+def test_phase_entry_point_equals_the_whole_call(dg):
+    import torch
+    A = wl.rmat_csr(scale=13, avg_degree=16, seed=5)
+    X = wl.dense_matrix(A.K, 4, "uniform", seed=2)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, 4, A.rowptr, A.colidx, A.vals, X)
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    for algo in range(4):
+        dY = torch.full((A.M, 4), float("nan"), device="cuda:0")
+        dg.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo, dg.PHASE_PREPARE)
+        dg.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo, dg.PHASE_MAIN)
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+        assert ok, (ALGO_NAMES[algo], worst)
+    L = dg.lib()
+    assert L.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(),
+                                 dX.data_ptr(), dY.data_ptr(), -1, 0, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(),
+                                 dX.data_ptr(), dY.data_ptr(), 0, 5, None) == dg.ERR_INVALID_ARG
+
+
+def test_gather_probe_sums_every_gathered_value(dg):
+    import torch
+    n, K = 1000003, 5000
+    idx = torch.randint(0, K, (n,), dtype=torch.int32, device="cuda:0")
+    x = torch.randint(-4, 5, (K,), device="cuda:0").float()          # small integers: sums are exact
+    out = torch.empty(dg.dgsp_gather_probe_out_len(), device="cuda:0")
+    dg.dgsp_gather_probe(out, x, idx)
+    torch.cuda.synchronize()
+    assert out.double().sum().item() == x[idx.long()].double().sum().item()
