@@ -81,7 +81,7 @@ int launch_rs_pr(const Problem& p) {
     const int logG = p.nnz >= 0 ? pr_lanes_log2(p.nnz, p.M) : -1;
     // one wave per row group when lanes-per-row is known; else assume the
     // finest split the kernel may choose (2 lanes per row) and let waves stride
-    const int rows_per_wave = kWave >> (logG >= 0 ? logG : 1);
+    const int rows_per_wave = (kWave >> (logG >= 0 ? logG : 1)) * kRsPrUnroll;
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));

@@ -26,7 +26,8 @@ namespace dgsp {
 // private partial sums, and the group is folded with the DPP scan (a plain
 // merge tree is the special case of the segmented scan with fixed-width
 // segments).  logG < 0 asks the kernel to derive it from rowptr[M] / M.
-// For N > V the columns are processed V at a time.
+// A wave keeps kRsPrUnroll row groups in flight.  For N > V the columns are
+// processed V at a time.
 
 __host__ __device__ __forceinline__ int pr_lanes_log2(long long nnz, long long M) {
     // lanes per row ~ average row length, rounded up to a power of two in [2, 64]
@@ -36,12 +37,15 @@ __host__ __device__ __forceinline__ int pr_lanes_log2(long long nnz, long long M
     return lg;
 }
 
+constexpr int kRsPrUnroll = 4;   // row groups a wave keeps in flight
+
 template <int V>
 __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG_in) {
+    constexpr int U = kRsPrUnroll;
     const int lane = lane_id();
     const int logG = logG_in >= 0 ? logG_in : pr_lanes_log2(rowptr[M], M);
     const int G = 1 << logG;
@@ -49,44 +53,66 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* 
     const int rows_per_wave = kWave >> logG;
     const unsigned nwaves = gridDim.x * kWavesPerBlock;
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
-    const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;   // row groups of one wave each
+    // a wave step covers U * rows_per_wave consecutive rows: U independent load -> gather -> reduce chains
+    const unsigned rows_per_step = (unsigned)(U * rows_per_wave);
+    const unsigned nsteps = ((unsigned)M + rows_per_step - 1) / rows_per_step;
 
-    // XCD-contiguous and interleaved: wave gw of the nwaves takes row groups
-    // q*nwaves + gw.  Consecutive waves (same block, same XCD) take consecutive rows.
-    for (unsigned rg = gw; rg < ngroups; rg += nwaves) {
-        const long long row = (long long)rg * rows_per_wave + (lane >> logG);
-        const bool live = row < M;
-        unsigned rs = 0, re = 0;
-        if (live) { rs = (unsigned)rowptr[row]; re = (unsigned)rowptr[row + 1]; }
-        for (int n0 = 0; n0 < N; n0 += V) {
-            float acc[V];
+    for (int n0 = 0; n0 < N; n0 += V) {
+        for (unsigned st = gw; st < nsteps; st += nwaves) {
+            long long row[U]; unsigned rs[U], re[U];
 #pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-            // four independent gathers in flight per lane
-            for (unsigned p = rs + gl; p < re; p += 4u * G) {
-                int c[4]; float a[4]; float x[4][V];
+            for (int u = 0; u < U; ++u) {
+                row[u] = (long long)st * rows_per_step + u * rows_per_wave + (lane >> logG);
+                rs[u] = 0; re[u] = 0;
+                if (row[u] < M) { rs[u] = (unsigned)rowptr[row[u]]; re[u] = (unsigned)rowptr[row[u] + 1]; }
+            }
+            float acc[U][V];
+            int c[U]; float a[U];
+            // first entry of every lane: for rows no longer than the group this is all there is
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const unsigned q = p + (unsigned)u * G;
-                    const bool ok = q < re;
-                    c[u] = ok ? colidx[q] : -1;
-                    a[u] = ok ? vals[q] : 0.0f;
+            for (int u = 0; u < U; ++u) {
+                const unsigned p = rs[u] + gl;
+                const bool ok = p < re[u];
+                c[u] = ok ? stream_load(colidx + p) : -1;
+                a[u] = ok ? stream_load(vals + p) : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float x[V];
+                if (c[u] >= 0) load_vec<V>(X + (size_t)c[u] * N + n0, x);
+                else {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) x[i] = 0.0f;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (c[u] >= 0) load_vec<V>(X + (size_t)c[u] * N + n0, x[u]);
+                for (int i = 0; i < V; ++i) acc[u][i] = a[u] * x[i];
+            }
+            // the rest of longer rows, two gathers in flight per lane
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                for (unsigned p = rs[u] + gl + G; p < re[u]; p += 2u * G) {
+                    const unsigned q = p + G;
+                    const bool ok2 = q < re[u];
+                    const int c0 = stream_load(colidx + p);
+                    const float a0 = stream_load(vals + p);
+                    const int c1 = ok2 ? stream_load(colidx + q) : -1;
+                    const float a1 = ok2 ? stream_load(vals + q) : 0.0f;
+                    float x0[V], x1[V];
+                    load_vec<V>(X + (size_t)c0 * N + n0, x0);
+                    if (c1 >= 0) load_vec<V>(X + (size_t)c1 * N + n0, x1);
                     else {
 #pragma unroll
-                        for (int i = 0; i < V; ++i) x[u][i] = 0.0f;
+                        for (int i = 0; i < V; ++i) x1[i] = 0.0f;
                     }
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[u][i] = fmaf(a1, x1[i], fmaf(a0, x0[i], acc[u][i]));
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);
             }
-            segmented_scan<V>(acc, gl, lane, G);   // all 64 lanes arrive here together
-            if (live && gl == G - 1) store_vec<V>(Y + (size_t)row * N + n0, acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                segmented_scan<V>(acc[u], gl, lane, G);   // all 64 lanes arrive here together
+                if (row[u] < M && gl == G - 1) store_vec<V>(Y + (size_t)row[u] * N + n0, acc[u]);
+            }
         }
     }
 }
@@ -97,13 +123,16 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* 
 // ===========================================================================
 //
 // 2^logG lanes own a row and V*2^logG dense columns (lane gl owns columns
-// [cb*G*V + gl*V, +V)).  The group loads a slice of the row's (colidx, val)
-// pairs with coalesced loads, parks it in its private LDS slot, then every
-// lane walks the cached pairs and accumulates its own columns: the dense
-// accesses of a group are one contiguous 4*V*G-byte piece of a row of X.
+// [cb*G*V + gl*V, +V)); a wave owns the 64/G consecutive rows of its lane
+// groups.  Those rows' (colidx, val) pairs are one contiguous stretch of the
+// CSR arrays, so the whole wave stages it in LDS with coalesced loads, kRsSrTile
+// pairs at a time (with few lanes per row a group-by-group load would fetch a
+// handful of bytes per group).  Every group then walks the cached part of its
+// own row and accumulates its own columns: the dense accesses of a group are
+// one contiguous 4*V*G-byte piece of a row of X.
 // blockIdx.y selects the column block when N > 64*V.
 
-constexpr int kRsSrSlot = 512;   // cached pairs per wave
+constexpr int kRsSrTile = 512;   // cached pairs per wave and round
 
 template <int V>
 __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* __restrict__ rowptr,
@@ -111,18 +140,17 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG) {
-    __shared__ int s_col[kWavesPerBlock][kRsSrSlot];
-    __shared__ float s_val[kWavesPerBlock][kRsSrSlot];
+    constexpr int T = kRsSrTile;
+    __shared__ int s_col[kWavesPerBlock][T];
+    __shared__ float s_val[kWavesPerBlock][T];
     const int lane = lane_id();
     const int wib = wave_in_block();
+    int* cc = s_col[wib];
+    float* cv = s_val[wib];
     const int G = 1 << logG;
     const int gl = lane & (G - 1);
     const int g = lane >> logG;
     const int rows_per_wave = kWave >> logG;
-    const int S = G >= 8 ? G : 8;               // pairs cached per group and round
-    const int R = S >> logG;                    // loads per lane and round
-    int* cc = s_col[wib] + g * S;
-    float* cv = s_val[wib] + g * S;
 
     const long long n = ((long long)blockIdx.y * G + gl) * V;   // my first dense column
     const bool col_ok = n < N;
@@ -132,32 +160,38 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
     const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;
 
     for (unsigned rg = gw; rg < ngroups; rg += nwaves) {
-        const long long row = (long long)rg * rows_per_wave + g;
+        const long long row0 = (long long)rg * rows_per_wave;
+        const long long row = row0 + g;
         const bool live = row < M;
         unsigned rs = 0, re = 0;
         if (live) { rs = (unsigned)rowptr[row]; re = (unsigned)rowptr[row + 1]; }
+        const long long row_end = row0 + rows_per_wave < M ? row0 + rows_per_wave : M;
+        const unsigned ps = (unsigned)uniform((int)rs);                  // lane 0 holds row0
+        const unsigned pe = (unsigned)uniform(rowptr[row_end]);          // the wave's rows span [ps, pe)
         float acc[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = 0.0f;
 
-        for (unsigned base = rs; base < re; base += (unsigned)S) {
+        for (unsigned ws = ps; ws < pe; ws += (unsigned)T) {
             wave_lds_sync();                    // last round's readers are done
-            for (int i = 0; i < R; ++i) {
-                const int e = i * G + gl;
-                const unsigned p = base + (unsigned)e;
-                if (p < re) { cc[e] = stream_load(colidx + p); cv[e] = stream_load(vals + p); }
+#pragma unroll
+            for (int k = 0; k < T / kWave; ++k) {
+                const unsigned p = ws + (unsigned)(k * kWave + lane);
+                if (p < pe) { cc[k * kWave + lane] = stream_load(colidx + p); cv[k * kWave + lane] = stream_load(vals + p); }
             }
             wave_lds_sync();
-            const int cnt = (re - base) < (unsigned)S ? (int)(re - base) : S;
+            const unsigned we = pe - ws > (unsigned)T ? ws + T : pe;
+            const unsigned lo = rs > ws ? rs : ws;
+            const unsigned hi = re < we ? re : we;
             if (col_ok) {
-                for (int j = 0; j < cnt; j += 4) {
+                for (unsigned p0 = lo; p0 < hi; p0 += 4) {
                     float x[4][V]; float a[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        if (j + u < cnt) {
-                            const int c = cc[j + u];
-                            a[u] = cv[j + u];
-                            load_vec<V>(X + (size_t)c * N + n, x[u]);
+                        if (p0 + u < hi) {
+                            const int e = (int)(p0 + u - ws);
+                            a[u] = cv[e];
+                            load_vec<V>(X + (size_t)cc[e] * N + n, x[u]);
                         } else {
                             a[u] = 0.0f;
 #pragma unroll
