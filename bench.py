@@ -36,7 +36,9 @@ CACHE_BYTES = 256e6 + 32e6     # Infinity Cache + 8 x 4 MB L2: what rotation has
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on dgsp_copy_f32);
 # see profiles/.  None = not measured for that cell.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "nb_pr/rmat_spmv/N1": 201.4e6,   # profiles/nb_pr_kernel_rmat20_spmv.md: 194.6 MB fetched + 6.8 MB written
+}
 
 
 def algorithmic_bytes(A, N):
@@ -189,7 +191,7 @@ def variant_table(rot, steps, warmup):
     from paper_2106_16064_amd import binding as dg
     out = {}
     for algo in dg.ALGOS:
-        k = max(5, min(steps, 50))
+        k = max(5, min(steps, 20))
         ms = time_events(None, lambda i: rot.step(i, algo), k, 3)
         out[dg.dgsp_algo_name(algo)] = median(ms)
     return out

@@ -74,12 +74,17 @@ typedef struct {
  *              else nnz-balanced (the cv guard is an addition: the paper's
  *              parallel-side rule looks at avg_row only; set pr_cv_max to a
  *              huge value to get the paper's rule verbatim)
- *   sequential: cv_row > sr_cv_min -> nnz-balanced, else row-split            */
+ *   sequential: cv_row > sr_cv_min AND stdv_row > sr_stdv_min -> nnz-balanced,
+ *              else row-split (the paper's metric is cv_row alone; the second
+ *              condition is an addition: with short rows even a large cv_row
+ *              leaves no row long enough to stall a wave; set sr_stdv_min to 0
+ *              for the paper's rule verbatim)                                  */
 typedef struct {
     int64_t n_parallel_max;
     double pr_avg_row_min;
     double pr_cv_max;
     double sr_cv_min;
+    double sr_stdv_min;
 } dgsp_thresholds_t;
 
 /*
@@ -133,8 +138,7 @@ int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N,
                        const float *X, float *Y, int *chosen, void *stream);
 
 /*
- * Kernel-selection rules of Section 2.2 (Figure "Adaptive strategy to select
- * kernels"): first N decides parallel vs sequential reduction, then avg_row
+ * Kernel-selection rules of Section 2.2 (the decision-tree figure): first N decides parallel vs sequential reduction, then avg_row
  * (parallel side) or stdv_row / avg_row (sequential side) decides whether to
  * balance by non-zeros.  Pure host function; returns a dgsp_algo_t in 0..3, or
  * DGSP_AUTO (-1) if features is NULL or N < 1.
@@ -147,8 +151,8 @@ void dgsp_get_thresholds(dgsp_thresholds_t *out);
 void dgsp_set_thresholds(const dgsp_thresholds_t *in);
 
 /*
- * Row-length statistics from a HOST copy of rowptr (Section 2.2's "low-cost"
- * features: one pass over M+1 integers, two accumulators).  Returns
+ * Row-length statistics from a HOST copy of rowptr (the cheap features of
+ * Section 2.2: one pass over M+1 integers, two accumulators).  Returns
  * DGSP_ERR_INVALID_ARG if M < 0, a pointer is NULL, rowptr[0] != 0 or rowptr
  * decreases.  M == 0 gives all-zero features.
  */

@@ -206,9 +206,10 @@ int launch_nb_sr(const Problem& p) {
 // no threshold values, Section 2.2).
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
-    /* pr_avg_row_min  */ 32.0,
-    /* pr_cv_max       */ 0.5,
-    /* sr_cv_min       */ 1.0,
+    /* pr_avg_row_min  */ 0.0,
+    /* pr_cv_max       */ 4.0,
+    /* sr_cv_min       */ 0.3,
+    /* sr_stdv_min     */ 30.0,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
@@ -277,7 +278,7 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;
     }
     // sequential reduction: balance only when stdv_row / avg_row says rows are uneven
-    return f->cv_row > t.sr_cv_min ? DGSP_NB_SR : DGSP_RS_SR;
+    return (f->cv_row > t.sr_cv_min && f->stdv_row > t.sr_stdv_min) ? DGSP_NB_SR : DGSP_RS_SR;
 }
 
 extern "C" void dgsp_get_thresholds(dgsp_thresholds_t* out) {

@@ -98,10 +98,10 @@ __device__ __forceinline__ float stream_load(const float* p) { return __builtin_
 // paper Section 2.1.1)
 // ---------------------------------------------------------------------------
 //
-// The paper runs a prefix-sum network over the lanes of a warp whose
-// operator is "add if the two elements carry the same row index".  Along a
-// run of CSR entries row indices never decrease, so "same row" is the same as
-// "no segment head in between".  Each lane therefore needs one number,
+// The paper runs a prefix-sum network over the lanes of a warp in which two
+// elements are added only if they carry the same row index.  Along a run of
+// CSR entries row indices never decrease, so two lanes share a row exactly
+// when no segment head lies between them.  Each lane therefore needs one number,
 //     h = how many lanes directly below it belong to its segment,
 // and a partner at distance d is added iff h >= d.  The network is the
 // canonical gfx9 wave64 scan: row_shr 1,2,4,8 inside each row of 16 lanes,

@@ -133,6 +133,10 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* 
 // blockIdx.y selects the column block when N > 64*V.
 
 constexpr int kRsSrTile = 512;   // cached pairs per wave and round
+#ifndef DGSP_SR_DEPTH
+#define DGSP_SR_DEPTH 4
+#endif
+constexpr int kSrDepth = DGSP_SR_DEPTH;   // dense-row loads a lane keeps in flight in the sequential kernels
 
 template <int V>
 __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* __restrict__ rowptr,
@@ -184,10 +188,10 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
             const unsigned lo = rs > ws ? rs : ws;
             const unsigned hi = re < we ? re : we;
             if (col_ok) {
-                for (unsigned p0 = lo; p0 < hi; p0 += 4) {
-                    float x[4][V]; float a[4];
+                for (unsigned p0 = lo; p0 < hi; p0 += kSrDepth) {
+                    float x[kSrDepth][V]; float a[kSrDepth];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
+                    for (int u = 0; u < kSrDepth; ++u) {
                         if (p0 + u < hi) {
                             const int e = (int)(p0 + u - ws);
                             a[u] = cv[e];
@@ -199,7 +203,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
+                    for (int u = 0; u < kSrDepth; ++u)
 #pragma unroll
                         for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);
                 }
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
 // nnz-balanced kernels: common partition
 // ===========================================================================
 //
-// The paper gives each warp "a fixed number of non-zeros" (Section 2.1.1).
+// The paper hands every warp the same count of stored entries (Section 2.1.1).
 // Counting only stored entries leaves one hole: a stretch of (nearly) empty
 // rows puts an unbounded number of row boundaries into one share.  So the
 // unit of work here is the *item* of the merge path of Merrill & Garland, which the
@@ -334,9 +338,10 @@ constexpr unsigned kNoRow = 0xffffffffu;
 //      leading part, stores the rows that lie inside it, and opens a new
 //      segment with its trailing part.
 //   4. The open row's running sum across lanes is the paper's segment
-//      reduction: the wave64 DPP scan whose operator is "add unless a row
-//      boundary lies in between" (one scan per tile instead of one per 64
-//      entries).  The lanes that hold a boundary "dump" the finished rows.
+//      reduction: the wave64 DPP scan that adds a partner lane's value only
+//      when no row boundary lies in between (one scan per tile instead of
+//      one per 64 entries).  The lanes that hold a boundary write out the
+//      finished rows.
 //   5. The sum still open at the end of a tile is handed to the chunk's next
 //      tile in a register; only the two ends of a chunk can need an atomic add.
 // The loads of the next tile are issued before the current tile is reduced.
@@ -580,7 +585,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
     const long long n = ((long long)blockIdx.y * G + gl) * V;
     const bool col_ok = n < N;
 
-    const ChunkPlan plan = plan_chunks(rowptr, M, W);     // chunks are whole tiles: runs stay aligned to U
+    const ChunkPlan plan = plan_chunks(rowptr, M, U);     // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
@@ -654,10 +659,10 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                 }
             };
 
-            for (unsigned p0 = j; p0 < j_end; p0 += 4) {
-                float x[4][V]; float a[4];
+            for (unsigned p0 = j; p0 < j_end; p0 += kSrDepth) {
+                float x[kSrDepth][V]; float a[kSrDepth];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kSrDepth; ++u) {
                     const unsigned p = p0 + u;
                     if (p < j_end) {
                         const int e = (int)(p - js);
@@ -670,7 +675,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kSrDepth; ++u) {
                     const unsigned p = p0 + u;
                     if (p < j_end) {
                         flush_rows_ending_at(p);             // rows that end before entry p

@@ -210,7 +210,7 @@ def test_balanced_kernels_agree_with_themselves(dg):
 def test_auto_entry_point_runs_the_selected_kernel(dg):
     import torch
     for A, N in ((wl.sweep_csr(1 << 14, 64, "fixed", 0), 1), (wl.sweep_csr(1 << 14, 4, "zipf", 0), 2),
-                 (wl.sweep_csr(1 << 14, 16, "poisson", 0), 64), (wl.sweep_csr(1 << 14, 16, "zipf", 0), 64)):
+                 (wl.sweep_csr(1 << 14, 16, "poisson", 0), 64), (wl.sweep_csr(1 << 14, 64, "zipf", 0), 64)):
         X = wl.dense_matrix(A.K, N, "uniform", seed=1)
         dA = dg.DeviceCsr(A)
         dX = torch.from_numpy(X).cuda()

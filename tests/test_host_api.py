@@ -72,7 +72,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0)      # the paper's rule verbatim (no cv guard)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0)      # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -88,6 +88,10 @@ def test_selection_rules_follow_the_decision_tree():
         dg.dgsp_set_thresholds(t)
         assert dg.dgsp_select_algo(feat(64, 5.0), 1) == dg.NB_PR
         assert dg.dgsp_select_algo(feat(64, 0.1), 1) == dg.RS_PR
+        t.sr_stdv_min = 30.0                                               # the added short-row guard
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(feat(4, 1.5), 64) == dg.RS_SR           # stdv 6: rows too short to matter
+        assert dg.dgsp_select_algo(feat(64, 1.5), 64) == dg.NB_SR          # stdv 96
         t.n_parallel_max = 8
         dg.dgsp_set_thresholds(t)
         assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_PR
