@@ -161,12 +161,13 @@ template <int V, int KQ>
 int launch_nb_pr_v(const Problem& p) {
     constexpr unsigned tile = kWave * 4 * KQ;
     const unsigned col_groups = (unsigned)(p.N / V);
-    if (col_groups > 65535u) return DGSP_ERR_INVALID_ARG;
+    // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
+    if (col_groups > 65535u || p.N > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>)), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
 }
 

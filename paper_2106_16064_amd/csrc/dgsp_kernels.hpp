@@ -331,80 +331,149 @@ constexpr unsigned kNoRow = 0xffffffffu;
 //   2. The products go through LDS once to change hands: afterwards lane l
 //      holds the products of the E consecutive entries E*l ... and reduces them
 //      in order in registers.
-//   3. Row ends are scattered into LDS as "row i ends after entry q" marks, so
+//   3. Row ends are scattered into LDS as marks (row i ends after entry q), so
 //      a lane sees its own boundaries with one 16-byte LDS read.  A lane
 //      without a boundary contributes its whole sum to the row that is open
 //      across lanes; a lane with boundaries closes that open row with its
-//      leading part, stores the rows that lie inside it, and opens a new
+//      leading part, finishes the rows that lie inside it, and opens a new
 //      segment with its trailing part.
 //   4. The open row's running sum across lanes is the paper's segment
 //      reduction: the wave64 DPP scan that adds a partner lane's value only
 //      when no row boundary lies in between (one scan per tile instead of
-//      one per 64 entries).  The lanes that hold a boundary write out the
-//      finished rows.
-//   5. The sum still open at the end of a tile is handed to the chunk's next
+//      one per 64 entries).
+//   5. The rows that end in a tile are consecutive, so finished sums are put
+//      into LDS by row and written out together: lane l stores row is + l.
+//      Rows without entries keep the zero the buffer was cleared to.
+//   6. The sum still open at the end of a tile is handed to the chunk's next
 //      tile in a register; only the two ends of a chunk can need an atomic add.
-// The loads of the next tile are issued before the current tile is reduced.
+//
+// Memory operations inside the tile loop are unconditional: loads clamp their
+// index and mask the value afterwards, the row store is a buffer store whose
+// offset is pushed out of range for lanes that have nothing to write (the
+// buffer unit drops those).  With no branch around them the outstanding-
+// operation counter can be waited on exactly, which is what lets the next
+// tile's loads stay in flight while this tile is reduced.
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
+constexpr unsigned kBufferFlags = 0x00020000u;      // raw 32-bit buffer descriptor, dword 3
+constexpr unsigned kOutOfRange = 0xffffffffu;
+
+// Descriptor for `bytes` bytes starting at p (clamped to the 4 GB a descriptor can span).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, unsigned long long bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0,
+                                             bytes > 0xffffffffull ? 0xffffffffu : (unsigned)bytes, kBufferFlags);
+}
+
+// Loads V consecutive floats at byte_offset; lanes whose offset is out of range get zeros and
+// cause no memory traffic.  `aux` 2 marks the load non-temporal.
+template <int V>
+__device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V]) {
+    if constexpr (V == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    } else if constexpr (V == 2) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, 0));
+        x[0] = t.x; x[1] = t.y;
+    } else {
+        x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, 0));
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
+    if constexpr (V == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const f4 t = {x[0], x[1], x[2], x[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
+    } else if constexpr (V == 2) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const f2 t = {x[0], x[1]};
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, 0);
+    }
+}
+
 template <int V, int KQ>
-__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y) {
     constexpr int E = 4 * KQ;
     constexpr int W = kWave * E;
-    __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W] = "ends before the tile's first entry"
-    __shared__ float s_prod[kWavesPerBlock][W * V];
+    __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the tile's first entry
+    __shared__ float s_buf[kWavesPerBlock][W * V];      // products, then the tile's row results
     const int lane = lane_id();
     const int wib = wave_in_block();
     unsigned* bnd = s_bnd[wib];
-    float* prod = s_prod[wib];
+    float* buf = s_buf[wib];
     const int n0 = blockIdx.y * V;
+
     const ChunkPlan plan = plan_chunks(rowptr, M, kWave);
     const unsigned nnz = plan.nnz;
+    const unsigned long long y_elems = (unsigned long long)M * (unsigned)N;
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
-    struct { unsigned d0, d1; } mr;
-    if (!plan.range(sub, mr.d0, mr.d1)) break;
+    unsigned d0, d1;
+    if (!plan.range(sub, d0, d1)) break;
 
-    int is = wave_merge_rows_before(rowptr, M, mr.d0, lane);   // rows that ended before my chunk
-    unsigned js = mr.d0 - (unsigned)is;                        // entries consumed before my chunk
+    if (nnz == 0) {
+        // nothing stored: every item is a row end; my rows are [d0, d1)
+        float zero[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+        for (unsigned r = d0 + lane; r < d1; r += kWave) store_vec<V>(Y + (size_t)r * N + n0, zero);
+        continue;
+    }
+
+    int is = wave_merge_rows_before(rowptr, M, d0, lane);   // rows that ended before my chunk
+    unsigned js = d0 - (unsigned)is;                        // entries consumed before my chunk
     // the first row to end in my chunk started before it?  then its sum is shared with another wave
     const int r_first = is;
-    const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < mr.d0;
+    const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < d0;
 
-    auto close_row = [&](int row, const float (&val)[V]) {
-        float* y = Y + (size_t)row * N + n0;
-        if (first_split && row == r_first) atomic_add_vec<V>(y, val); else store_vec<V>(y, val);
-    };
-    // entries of a tile starting at entry `from`: at most W, the real count is known later
-    auto load_entries = [&](unsigned from, int (&c)[E], float (&a)[E]) {
+    // entries of a tile starting at entry `from`: at most W.  The descriptor ends at the arrays' end,
+    // so lanes past it load nothing; `on` = false switches the whole load off.
+    auto load_entries = [&](unsigned from, bool on, int (&c)[E], float (&a)[E]) {
+        const unsigned long long bytes = on ? (unsigned long long)(nnz - from) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + from, bytes);
+        const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + from, bytes);
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            const unsigned p = from + (unsigned)(e * kWave + lane);
-            const bool ok = p < nnz;
-            c[e] = ok ? stream_load(colidx + p) : 0;
-            a[e] = ok ? stream_load(vals + p) : 0.0f;
+            const unsigned off = (unsigned)(e * kWave + lane) * 4u;
+            c[e] = (int)__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 2);
+            a[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra, off, 0, 2));
         }
     };
-    // start and end offset of row `first + lane` (the first 64 candidates for "ends in the tile")
-    auto load_row_bounds = [&](int first, unsigned& start, unsigned& end) {
-        const long long r = (long long)first + lane;
-        start = 0; end = 0;
-        if (r < M) { start = (unsigned)rowptr[r]; end = (unsigned)rowptr[r + 1]; }
+    // start and end offset of row `first + lane`; rows past the last one read as 0, 0
+    auto load_row_bounds = [&](int first, bool on, unsigned& start, unsigned& end) {
+        const unsigned long long bytes = (on && first < M) ? (unsigned long long)(M + 1 - first) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t rr = make_buffer(rowptr + first, bytes);
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const u2 t = __builtin_amdgcn_raw_buffer_load_b64(rr, (unsigned)lane * 4u, 0, 0);
+        start = t.x; end = t.y;
     };
+    // the dense operand: byte offsets of X rows fit 32 bits unless X is 4 GB or more
+    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const bool x_small = x_bytes <= 0xffffffffull;
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
 
     float carry[V];      // running sum of the row that is open at the tile boundary (wave-uniform)
 #pragma unroll
     for (int i = 0; i < V; ++i) carry[i] = 0.0f;
 
-    int c[E]; float a[E]; unsigned w_start, w_end;
-    load_entries(js, c, a);
-    load_row_bounds(is, w_start, w_end);
+    int c[E]; float a[E]; unsigned w_start, w_end;   // w_start is only there for the paired load
+    load_row_bounds(is, true, w_start, w_end);
+    load_entries(js, true, c, a);
 
-    for (unsigned ds = mr.d0; ds < mr.d1; ds += W) {
-        const unsigned de = (mr.d1 - ds > (unsigned)W) ? ds + W : mr.d1;
+    for (unsigned ds = d0; ds < d1; ds += W) {
+        const unsigned de = (d1 - ds > (unsigned)W) ? ds + W : d1;
 
         // ---- row ends of this tile -> LDS marks
         wave_lds_sync();                                   // the previous tile's readers are done
@@ -415,73 +484,60 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
         wave_lds_sync();
         int ie = is;
         // marks the rows of one batch of 64 candidates that end in the tile; returns how many did
-        auto mark_row_ends = [&](int m, unsigned start, unsigned end) {
+        auto mark_row_ends = [&](int m, unsigned end) {
             const long long r = (long long)is + m * kWave + lane;
             const bool ends = r < M && (unsigned)r + end < de;     // the row's end marker is inside the tile
             if (ends) {
                 const unsigned q = end - js;               // it ends after entry q-1 of the tile
                 atomicMin(bnd + (q ? q - 1 : (unsigned)W), (unsigned)(r - is));
-                // empty rows other than the tile's first get their zeros here: no sum ever closes them
-                if (r > is && start == end) {
-                    float zero[V];
-#pragma unroll
-                    for (int i = 0; i < V; ++i) zero[i] = 0.0f;
-                    store_vec<V>(Y + (size_t)r * N + n0, zero);
-                }
             }
             return (int)__popcll(__ballot(ends));
         };
-        int cnt = mark_row_ends(0, w_start, w_end);        // the first 64 candidates were loaded a tile ago
+        int cnt = mark_row_ends(0, w_end);                 // the first 64 candidates were loaded a tile ago
         ie += cnt;
         if (cnt == kWave) {
             // a tile crowded with row ends (at most W of them): fetch all remaining candidates at once
             unsigned ms[E - 1], me[E - 1];
 #pragma unroll
-            for (int m = 1; m < E; ++m) load_row_bounds(is + m * kWave, ms[m - 1], me[m - 1]);
+            for (int m = 1; m < E; ++m) load_row_bounds(is + m * kWave, true, ms[m - 1], me[m - 1]);
 #pragma unroll
             for (int m = 1; m < E; ++m) {
-                if (cnt == kWave) { cnt = mark_row_ends(m, ms[m - 1], me[m - 1]); ie += cnt; }
+                if (cnt == kWave) { cnt = mark_row_ends(m, me[m - 1]); ie += cnt; }
             }
         }
         const unsigned je = de - (unsigned)ie;             // entries [js, je) belong to the tile
         const int nE = (int)(je - js);
+        const int nrows = ie - is;                         // rows [is, ie) end in the tile
         wave_lds_sync();
 
         // ---- gather for this tile, then the next tile's loads (they stay in flight during the reduction)
         float x[E][V];
+        if (x_small) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            if (e * kWave + lane < nE) load_vec<V>(X + (size_t)c[e] * N + n0, x[e]);
-            else {
+            for (int e = 0; e < E; ++e)
+                buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)N * 4u : kOutOfRange, x[e]);
+        } else {
 #pragma unroll
-                for (int i = 0; i < V; ++i) x[e][i] = 0.0f;
-                a[e] = 0.0f;
-            }
+            for (int e = 0; e < E; ++e) load_vec<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * N + n0, x[e]);
         }
-        int c2[E]; float a2[E]; unsigned w_start2 = 0, w_end2 = 0;
-        const bool more = mr.d1 - ds > (unsigned)W;
-        if (more) {
-            load_entries(je, c2, a2);
-            load_row_bounds(ie, w_start2, w_end2);
-        }
-
-        // ---- rows that end before the tile's first entry take the sum carried in
-        const unsigned b_in = bnd[W];
-        if (b_in != kNoRow) {
-            if (lane == 0) close_row(is + (int)b_in, carry);
-#pragma unroll
-            for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+        int c2[E]; float a2[E]; unsigned w_start2, w_end2;
+        {
+            const bool more = d1 - ds > (unsigned)W;       // past the chunk's last tile the loads are switched off
+            load_row_bounds(ie, more, w_start2, w_end2);
+            load_entries(je, more, c2, a2);
         }
 
         // ---- products change hands through LDS: entry 64e+l -> lane (64e+l)/E
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             float p[V];
+            const bool mine = e * kWave + lane < nE;
 #pragma unroll
-            for (int i = 0; i < V; ++i) p[i] = a[e] * x[e][i];
-            store_vec<V>(prod + (size_t)(e * kWave + lane) * V, p);
+            for (int i = 0; i < V; ++i) p[i] = mine ? a[e] * x[e][i] : 0.0f;
+            store_vec<V>(buf + (size_t)(e * kWave + lane) * V, p);
         }
         wave_lds_sync();
+        const unsigned b_in = bnd[W];
         unsigned b[E];
 #pragma unroll
         for (int k = 0; k < KQ; ++k) {
@@ -490,7 +546,23 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
         }
         float pr[E][V];
 #pragma unroll
-        for (int e = 0; e < E; ++e) load_vec<V>(prod + (size_t)(E * lane + e) * V, pr[e]);
+        for (int e = 0; e < E; ++e) load_vec<V>(buf + (size_t)(E * lane + e) * V, pr[e]);
+        wave_lds_sync();                                   // products are in registers: the buffer is free
+
+        // ---- the tile's row results: cleared, so rows without entries come out as zeros
+        for (int k = 0; k * kWave < nrows; ++k) {
+            float zero[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+            store_vec<V>(buf + (size_t)(k * kWave + lane) * V, zero);
+        }
+        wave_lds_sync();
+        // rows that end before the tile's first entry take the sum carried in
+        if (b_in != kNoRow) {
+            if (lane == 0) store_vec<V>(buf + (size_t)b_in * V, carry);
+#pragma unroll
+            for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+        }
 
         // ---- in-lane reduction over my E consecutive entries
         float s[V], head[V];
@@ -507,7 +579,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
 #pragma unroll
                     for (int i = 0; i < V; ++i) head[i] = s[i];
                 } else {
-                    close_row(is + (int)b[e], s);          // a row that begins and ends inside this lane
+                    store_vec<V>(buf + (size_t)b[e] * V, s);   // a row that begins and ends inside this lane
                 }
 #pragma unroll
                 for (int i = 0; i < V; ++i) s[i] = 0.0f;
@@ -518,22 +590,41 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, int N, const int* 
         const bool flagged = head_row != kNoRow;
         const int head_lane = (int)wave_max_scan(flagged ? (unsigned)lane : 0u);
         segmented_scan<V>(s, lane - head_lane, lane);      // s: sum of the open row up to and including my lane
-        if (__ballot(flagged)) {                           // wave-uniform
+        {
             float closing[V];
 #pragma unroll
             for (int i = 0; i < V; ++i) closing[i] = dpp_or_zero<kDppWaveShr1, 0xf>(s[i]) + head[i];
-            if (flagged) close_row(is + (int)head_row, closing);
+            if (flagged) store_vec<V>(buf + (size_t)head_row * V, closing);
         }
 #pragma unroll
         for (int i = 0; i < V; ++i) carry[i] = read_lane(s[i], kWave - 1);
+        wave_lds_sync();
+
+        // ---- write the rows [is, ie) out, lane l row is + l: the first 64 with one unconditional
+        //      buffer store, further batches (tiles crowded with short rows) in a loop
+        {
+            const unsigned long long first_elem = (unsigned long long)is * (unsigned)N + (unsigned)n0;
+            const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
+            __amdgpu_buffer_rsrc_t yrows = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left, kBufferFlags);
+            auto write_rows = [&](int k) {
+                const int t = k * kWave + lane;                     // local row
+                float val[V];
+                load_vec<V>(buf + (size_t)t * V, val);
+                const bool live = t < nrows;
+                const bool shared = first_split && is + t == r_first;   // finished by an atomic add instead
+                buffer_store_vec<V>(yrows, (live && !shared) ? (unsigned)t * (unsigned)N * 4u : kOutOfRange, val);
+                if (live && shared) atomic_add_vec<V>(Y + (size_t)(is + t) * N + n0, val);
+            };
+            write_rows(0);
+            for (int k = 1; k * kWave < nrows; ++k) write_rows(k);
+        }
 
         is = ie;
         js = je;
-        if (more) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) { c[e] = c2[e]; a[e] = a2[e]; }
-            w_start = w_start2; w_end = w_end2;
-        }
+        for (int e = 0; e < E; ++e) { c[e] = c2[e]; a[e] = a2[e]; }
+        w_start = w_start2; w_end = w_end2;
     }
 
     // the row still open at the end of my chunk is finished by another wave
