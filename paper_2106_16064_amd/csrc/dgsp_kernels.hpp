@@ -468,11 +468,14 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 #pragma unroll
     for (int i = 0; i < V; ++i) carry[i] = 0.0f;
 
-    int c[E]; float a[E]; unsigned w_start, w_end;   // w_start is only there for the paired load
-    load_row_bounds(is, true, w_start, w_end);
-    load_entries(js, true, c, a);
+    // two register sets take turns: while one tile is reduced the other set receives the next tile
+    int cA[E], cB[E]; float aA[E], aB[E]; unsigned wA, wB, w_unused;
+    load_row_bounds(is, true, w_unused, wA);
+    load_entries(js, true, cA, aA);
+    unsigned ds = d0;
 
-    for (unsigned ds = d0; ds < d1; ds += W) {
+    // one tile: consumes (c, a, w_end), leaves the next tile's loads in flight in (c2, a2, w_end2)
+    auto do_tile = [&](int (&c)[E], float (&a)[E], unsigned w_end, int (&c2)[E], float (&a2)[E], unsigned& w_end2) {
         const unsigned de = (d1 - ds > (unsigned)W) ? ds + W : d1;
 
         // ---- row ends of this tile -> LDS marks
@@ -520,10 +523,9 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 #pragma unroll
             for (int e = 0; e < E; ++e) load_vec<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * N + n0, x[e]);
         }
-        int c2[E]; float a2[E]; unsigned w_start2, w_end2;
         {
             const bool more = d1 - ds > (unsigned)W;       // past the chunk's last tile the loads are switched off
-            load_row_bounds(ie, more, w_start2, w_end2);
+            load_row_bounds(ie, more, w_unused, w_end2);
             load_entries(je, more, c2, a2);
         }
 
@@ -622,9 +624,12 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 
         is = ie;
         js = je;
-#pragma unroll
-        for (int e = 0; e < E; ++e) { c[e] = c2[e]; a[e] = a2[e]; }
-        w_start = w_start2; w_end = w_end2;
+        ds += W;
+    };
+    while (ds < d1) {
+        do_tile(cA, aA, wA, cB, aB, wB);
+        if (ds >= d1) break;
+        do_tile(cB, aB, wB, cA, aA, wA);
     }
 
     // the row still open at the end of my chunk is finished by another wave
