@@ -60,6 +60,8 @@ def make_workload(name, n):
                      "GNN-style SpMM: R-MAT 2^20 vertices, avg degree 16, row-normalised"),
         "stencil": (lambda: wl.stencil27_csr(128, seed=0), "uniform", "27-point stencil on 128^3"),
         "tiny": (lambda: wl.poisson_csr(4096, 4096, 8.0, seed=0), "uniform", "tiny SpMM: 4096^2 Poisson(8)"),
+        "uniform64": (lambda: wl.sweep_csr(1 << 18, 64, "fixed", 0), "uniform",
+                      "sweep matrix: 2^18 rows of exactly 64 uniform-random columns"),
     }
     if name not in gens:
         raise SystemExit(f"unknown workload {name}")

@@ -120,13 +120,13 @@ int launch_rs_sr(const Problem& p) {
 
 // ---------------------------------------------------------------- balanced launches
 // Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: the chunk size the
-// main kernel derives for `parts` chunks rounded to `quantum` items.
-int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum) {
+// main kernel derives for `parts` chunks rounded to `quantum` items, cut into tiles of `tile` items.
+int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum, unsigned tile) {
     int logP = ilog2_ceil(p.N);
     if (logP > 6) logP = 6;
     const long long threads = (long long)p.M << logP;
     const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, logP);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, tile, logP);
     return DGSP_OK;
 }
 
@@ -165,7 +165,7 @@ int launch_nb_pr_v(const Problem& p) {
     if (col_groups > 65535u || p.N > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>)), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave)) return rc;
+        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave, 0)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
         DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
@@ -188,7 +188,7 @@ int launch_nb_sr_v(const Problem& p) {
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V>)), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 1u << logU, 0, 0)) return rc;
+        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 1u << logU, kNbSrTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
         DGSP_LAUNCH(nb_sr_kernel<V>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;

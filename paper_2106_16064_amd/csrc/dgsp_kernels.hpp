@@ -254,19 +254,26 @@ __device__ __forceinline__ unsigned merge_chunk_items(unsigned items, unsigned p
     return per ? per : quantum;
 }
 
-// Zeroes the rows that are split by a multiple of `unit` items.  unit == 0:
-// the unit is the chunk size for `parts` chunks (see merge_chunk_items).
+// Zeroes the rows whose items do not all lie in one piece of the partition.
+// unit > 0: pieces are the multiples of `unit` items.  unit == 0: pieces are
+// the chunks for `parts` chunks (see merge_chunk_items), cut further into
+// tiles of `tile` items counted from the chunk's start when tile > 0.
 // 2^logP consecutive threads share a row.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
-                                                             unsigned quantum, int logP) {
+                                                             unsigned quantum, unsigned tile, int logP) {
     const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
     const long long row = t >> logP;
     if (row >= M) return;
-    if (unit == 0) unit = merge_chunk_items((unsigned)rowptr[M] + (unsigned)M, parts, quantum);
     const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
     const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
-    if (first / unit == last / unit) return;
+    if (unit != 0) {
+        if (first / unit == last / unit) return;
+    } else {
+        const unsigned per = merge_chunk_items((unsigned)rowptr[M] + (unsigned)M, parts, quantum);
+        const unsigned c1 = first / per, c2 = last / per;
+        if (c1 == c2 && (tile == 0 || (first - c1 * per) / tile == (last - c1 * per) / tile)) return;
+    }
     float* y = Y + (size_t)row * N;
     for (int n = (int)(t & ((1 << logP) - 1)); n < N; n += 1 << logP) y[n] = 0.0f;
 }
@@ -649,9 +656,14 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 // end offsets of the rows that end in it.  Its 64/G lane groups then each walk
 // one run of U = W*G/64 consecutive items in order; lane gl of a group owns V
 // dense columns, so per entry a group reads one contiguous piece of a row of
-// X.  At a row end the accumulator is flushed: plain store if the row's items
-// all lie in the run, atomic add otherwise (prepare kernel, unit U).  Empty
-// rows flush a zero accumulator, which is how they get their zeros.
+// X.  At a row end the accumulator is flushed.  A row whose items all lie in
+// the run is stored directly (empty rows flush a zero accumulator, which is
+// how they get their zeros).  A row that crosses run boundaries inside the
+// tile is summed in LDS: every run adds its part to the slot named after the
+// run the row started in, and after the walk one group writes the slot out -
+// with a plain store if the row also ended inside the tile.  Only rows that
+// cross the tile's own ends go to memory with atomic adds (prepare kernel:
+// rows split by a tile boundary).
 // blockIdx.y selects the block of G*V dense columns.
 
 constexpr int kNbSrTile = 512;
@@ -664,18 +676,26 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG) {
     constexpr int W = kNbSrTile;
+    constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
     __shared__ int s_col[kWavesPerBlock][W];
     __shared__ float s_val[kWavesPerBlock][W];
-    __shared__ unsigned s_end[kWavesPerBlock][W + 4];   // end offsets of the rows ending in the tile
+    __shared__ unsigned short s_end[kWavesPerBlock][W + 8];   // end offsets (minus js) of the rows ending in the tile
+    __shared__ float s_slot[kWavesPerBlock][kSlotFloats];
+    __shared__ int s_slot_row[kWavesPerBlock][kWave + 4];   // row of each slot (-1: unused)
+    __shared__ int s_slot_end[kWavesPerBlock][kWave + 4];   // 1: the slot's row ended inside the tile
     const int lane = lane_id();
     const int wib = wave_in_block();
     int* cc = s_col[wib];
     float* cv = s_val[wib];
-    unsigned* ends = s_end[wib];
+    unsigned short* ends = s_end[wib];
+    float* slot_acc = s_slot[wib];
+    int* slot_row = s_slot_row[wib];
+    int* slot_end = s_slot_end[wib];
 
     const int G = 1 << logG;
     const int gl = lane & (G - 1);
     const int g = lane >> logG;
+    const int groups = kWave >> logG;
     const int logU = kNbSrLogTile - 6 + logG;
     const unsigned U = 1u << logU;
     const long long n = ((long long)blockIdx.y * G + gl) * V;
@@ -700,6 +720,11 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
             const unsigned p = js + (unsigned)e;
             if (p < nnz) { cc[e] = stream_load(colidx + p); cv[e] = stream_load(vals + p); }
         }
+        // slots for the rows that cross run boundaries inside the tile
+#pragma unroll
+        for (int k = 0; k < kSlotFloats / kWave; ++k) slot_acc[k * kWave + lane] = 0.0f;
+        slot_row[lane] = -1; slot_end[lane] = 0;
+        if (lane == 0) { slot_row[kWave] = -1; slot_end[kWave] = 0; }
         // end offsets of rows is, is+1, ... while their end marker is inside the tile
         int ie = is;
         for (int m = 0; m < W / kWave; ++m) {
@@ -708,7 +733,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
             if (r < M) {
                 const unsigned e = (unsigned)rowptr[r + 1];
                 in = (unsigned)r + e < de;
-                if (in) ends[m * kWave + lane] = e;
+                if (in) ends[m * kWave + lane] = (unsigned short)(e - js);
             }
             const int cnt = __popcll(__ballot(in));
             ie += cnt;
@@ -726,32 +751,39 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                 int lo = 0, hi = nrows;
                 while (lo < hi) {
                     const int mid = (lo + hi) >> 1;
-                    if ((unsigned)(is + mid) + ends[mid] < d) lo = mid + 1; else hi = mid;
+                    if ((unsigned)(is + mid) + js + ends[mid] < d) lo = mid + 1; else hi = mid;
                 }
                 return lo;
             };
             int t = rows_before(dg);                         // first row (local) to end at or after dg
             const int t_end = rows_before(dh);               // rows [t, t_end) end inside my run
-            unsigned j = dg - (unsigned)(is + t);            // first entry of my run
+            const unsigned j = dg - (unsigned)(is + t);      // first entry of my run
             const unsigned j_end = dh - (unsigned)(is + t_end);
-            unsigned next_end = t < nrows ? ends[t] : kNoRow;   // end offset of the current row
-            // the current row's first item lies before my run?  (its start offset is the previous row's end)
-            const unsigned cur_start = t == 0 ? rs_first : ends[t - 1];
-            bool split = (unsigned)(is + t) + cur_start < dg;
+            unsigned next_end = t < nrows ? js + ends[t] : kNoRow;   // end offset of the current row
+            // first item of the current row (its start offset is the previous row's end)
+            unsigned cur_first = (unsigned)(is + t) + (t == 0 ? rs_first : js + ends[t - 1]);
 
             float acc[V];
 #pragma unroll
             for (int i = 0; i < V; ++i) acc[i] = 0.0f;
 
+            // a partial sum of row is+t (it crosses my run's ends) goes to the slot of the run it started in
+            auto to_slot = [&](bool ended) {
+                const int s = cur_first < ds ? 0 : (int)((cur_first - ds) >> logU) + 1;
+                float* dst = slot_acc + (size_t)(s * G + gl) * V;
+#pragma unroll
+                for (int i = 0; i < V; ++i) atomicAdd(dst + i, acc[i]);
+                if (gl == 0) { slot_row[s] = is + t; if (ended) slot_end[s] = 1; }   // every writer of slot_row[s] writes the same row
+            };
             auto flush_rows_ending_at = [&](unsigned pos) {
                 while (next_end == pos && t < t_end) {
-                    float* y = Y + (size_t)((long long)is + t) * N + n;
-                    if (split) atomic_add_vec<V>(y, acc); else store_vec<V>(y, acc);
+                    if (cur_first < dg) to_slot(true);
+                    else store_vec<V>(Y + (size_t)((long long)is + t) * N + n, acc);
 #pragma unroll
                     for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-                    split = false;
+                    cur_first = (unsigned)(is + t) + 1 + next_end;      // the next row starts right after this end marker
                     ++t;
-                    next_end = t < nrows ? ends[t] : kNoRow;
+                    next_end = t < nrows ? js + ends[t] : kNoRow;
                 }
             };
 
@@ -781,11 +813,23 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                 }
             }
             flush_rows_ending_at(j_end);                     // rows whose end marker closes my run
-            // what is left belongs to a row that ends in a later run
-            bool any = false;
-#pragma unroll
-            for (int i = 0; i < V; ++i) any |= acc[i] != 0.0f;
-            if (any) atomic_add_vec<V>(Y + (size_t)((long long)is + t) * N + n, acc);
+            // what is left belongs to a row that goes on after my run (if the run held entries of it)
+            if ((unsigned)(is + t) + j_end > cur_first) to_slot(false);
+        }
+        wave_lds_sync();                                     // every run has added its parts
+
+        // one group per slot writes the rows that crossed run boundaries: slot g+1 by group g, slot 0 by group 0 too
+        if (col_ok) {
+            for (int s = (g == 0 ? 0 : g + 1); s <= g + 1 && s <= groups; ++s) {
+                const int row = slot_row[s];
+                if (row >= 0) {
+                    float val[V];
+                    load_vec<V>(slot_acc + (size_t)(s * G + gl) * V, val);
+                    float* y = Y + (size_t)row * N + n;
+                    // started inside the tile (s > 0) and ended inside it: nobody else has a part of this row
+                    if (s > 0 && slot_end[s]) store_vec<V>(y, val); else atomic_add_vec<V>(y, val);
+                }
+            }
         }
 
         js = de - (unsigned)ie;
