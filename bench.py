@@ -105,7 +105,7 @@ class Rotation:
         j = i % self.copies
         m = self.mats[j]
         dg.dgsp_spmm_csr_phase(m.M, m.K, self.N, m.nnz, m.rowptr, m.colidx, m.vals, self.X[j], self.Y[j],
-                               algo, phase)
+                               algo, phase, m.features)
 
 
 def time_steps(rot, algo, steps, warmup, warm=False):

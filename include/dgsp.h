@@ -65,6 +65,10 @@ typedef struct {
     int64_t M, K, nnz;
     double avg_row, stdv_row, cv_row;
     int64_t max_row, min_row;
+    double col_span; /* mean over non-empty rows of (largest - smallest column + 1) / K; 0 = unknown.
+                        Not part of the paper's rules: it does not change which kernel runs, only how
+                        many dense-row loads the sequential kernels keep in flight (a banded matrix,
+                        col_span <= 0.05, re-uses rows of X between neighbouring rows and wants more). */
 } dgsp_features_t;
 
 /* Selector thresholds (Section 2.2 says they are set empirically and prints no
@@ -160,6 +164,13 @@ int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t *rowptr_h
                                    dgsp_features_t *out);
 
 /*
+ * Same statistics plus col_span, from HOST copies of rowptr and colidx (one more
+ * pass, over the two ends of every sorted row; unsorted rows are scanned).
+ */
+int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t *rowptr_host,
+                                const int32_t *colidx_host, dgsp_features_t *out);
+
+/*
  * Measurement aid: the same multiplication, one step at a time.  The two
  * nnz-balanced kernels are two launches per call - a small "prepare" launch
  * (zeroes the rows that are later combined with atomic adds) and the main
@@ -170,12 +181,14 @@ int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t *rowptr_h
  *           DGSP_PHASE_MAIN     only the main kernel; the result is right only if
  *                               PREPARE for the same arguments ran before it on
  *                               the same stream
- * algo must be one of the four kernels (not DGSP_AUTO).
+ * algo must be one of the four kernels (not DGSP_AUTO).  `features` may be NULL;
+ * if given (host pointer) its nnz and col_span are used as in the adaptive call.
  */
 typedef enum { DGSP_PHASE_ALL = 0, DGSP_PHASE_PREPARE = 1, DGSP_PHASE_MAIN = 2 } dgsp_phase_t;
 int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
                         const int32_t *rowptr, const int32_t *colidx, const float *vals,
-                        const float *X, float *Y, int algo, int phase, void *stream);
+                        const float *X, float *Y, int algo, int phase,
+                        const dgsp_features_t *features, void *stream);
 
 /*
  * Measurement aid, not part of the method: out[t] = sum of x[idx[i]] over the

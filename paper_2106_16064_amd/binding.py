@@ -21,7 +21,7 @@ EXPORTS = (
     "dgsp_spmm_csr", "dgsp_spmm_csr_nnz", "dgsp_spmm_csr_auto", "dgsp_select_algo",
     "dgsp_get_thresholds", "dgsp_set_thresholds", "dgsp_features_from_rowptr_host",
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
-    "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len",
+    "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 
@@ -30,7 +30,7 @@ class Features(ctypes.Structure):
     """``dgsp_features_t``"""
     _fields_ = [("M", ctypes.c_int64), ("K", ctypes.c_int64), ("nnz", ctypes.c_int64),
                 ("avg_row", ctypes.c_double), ("stdv_row", ctypes.c_double), ("cv_row", ctypes.c_double),
-                ("max_row", ctypes.c_int64), ("min_row", ctypes.c_int64)]
+                ("max_row", ctypes.c_int64), ("min_row", ctypes.c_int64), ("col_span", ctypes.c_double)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -75,8 +75,10 @@ def lib():
         L.dgsp_set_thresholds.argtypes = [ctypes.POINTER(Thresholds)]
         L.dgsp_features_from_rowptr_host.restype = ci
         L.dgsp_features_from_rowptr_host.argtypes = [i64, i64, vp, ctypes.POINTER(Features)]
+        L.dgsp_features_from_csr_host.restype = ci
+        L.dgsp_features_from_csr_host.argtypes = [i64, i64, vp, vp, ctypes.POINTER(Features)]
         L.dgsp_spmm_csr_phase.restype = ci
-        L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, vp]
+        L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
         L.dgsp_gather_probe.restype = ci
         L.dgsp_gather_probe.argtypes = [vp, vp, vp, i64, vp]
         L.dgsp_gather_probe_out_len.restype = i64
@@ -137,11 +139,12 @@ def dgsp_spmm_csr_nnz(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, stream=Non
     _check(rc, "dgsp_spmm_csr_nnz")
 
 
-def dgsp_spmm_csr_phase(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, phase, stream=None):
+def dgsp_spmm_csr_phase(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, phase, features=None, stream=None):
     """One step of the multiplication (measurement aid): PHASE_PREPARE, PHASE_MAIN or PHASE_ALL."""
     _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
     rc = lib().dgsp_spmm_csr_phase(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
-                                   int(algo), int(phase), _stream(stream))
+                                   int(algo), int(phase), ctypes.byref(features) if features is not None else None,
+                                   _stream(stream))
     _check(rc, "dgsp_spmm_csr_phase")
 
 
@@ -194,6 +197,19 @@ def dgsp_features_from_rowptr_host(M, K, rowptr_host) -> Features:
     return f
 
 
+def dgsp_features_from_csr_host(M, K, rowptr_host, colidx_host) -> Features:
+    """Row statistics plus ``col_span`` from host copies of rowptr and colidx."""
+    import numpy as np
+    rp = np.ascontiguousarray(rowptr_host, dtype=np.int32)
+    ci = np.ascontiguousarray(colidx_host, dtype=np.int32)
+    if rp.size != M + 1 or ci.size < int(rp[-1] if rp.size else 0):
+        raise DgspError("rowptr needs M+1 entries and colidx rowptr[M]")
+    f = Features()
+    rc = lib().dgsp_features_from_csr_host(M, K, rp.ctypes.data, ci.ctypes.data if ci.size else None, ctypes.byref(f))
+    _check(rc, "dgsp_features_from_csr_host")
+    return f
+
+
 def dgsp_copy_f32(dst, src, n=None, stream=None):
     n = dst.numel() if n is None else n
     rc = lib().dgsp_copy_f32(_ptr(dst), _ptr(src), int(n), _stream(stream))
@@ -217,7 +233,7 @@ class DeviceCsr:
         self.rowptr = torch.from_numpy(A.rowptr).to(device)
         self.colidx = torch.from_numpy(A.colidx).to(device)
         self.vals = torch.from_numpy(A.vals).to(device)
-        self.features = dgsp_features_from_rowptr_host(A.M, A.K, A.rowptr)
+        self.features = dgsp_features_from_csr_host(A.M, A.K, A.rowptr, A.colidx)
 
     def spmm(self, X, algo=AUTO, Y=None, use_nnz=True, stream=None):
         """Y = A X.  ``algo=AUTO`` applies the selection rules to this matrix's features."""
@@ -228,7 +244,9 @@ class DeviceCsr:
         if algo == AUTO:
             dgsp_spmm_csr_auto(self.M, self.K, N, self.features, self.rowptr, self.colidx, self.vals, X, Y, stream)
         elif use_nnz:
-            dgsp_spmm_csr_nnz(self.M, self.K, N, self.nnz, self.rowptr, self.colidx, self.vals, X, Y, algo, stream)
+            # a named kernel with this matrix's hints (entry count, column span)
+            dgsp_spmm_csr_phase(self.M, self.K, N, self.nnz, self.rowptr, self.colidx, self.vals, X, Y, algo,
+                                PHASE_ALL, self.features, stream)
         else:
             dgsp_spmm_csr(self.M, self.K, N, self.rowptr, self.colidx, self.vals, X, Y, algo, stream)
         return Y

@@ -67,6 +67,7 @@ struct Problem {
     const int* rowptr; const int* colidx; const float* vals; const float* X; float* Y;
     hipStream_t stream;
     int phase = DGSP_PHASE_ALL;
+    double col_span = 0.0;   // mean column span of a row / K; 0 = unknown
 };
 
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
@@ -100,8 +101,22 @@ inline int sr_lanes_log2(long long N, int V) {
     return lg > 6 ? 6 : lg;
 }
 
-int launch_rs_sr(const Problem& p) {
-    const int V = vector_width(p.N, p.X, p.Y);
+// X can be addressed with 32-bit byte offsets (through a buffer descriptor)
+inline bool x_fits_descriptor(const Problem& p) {
+#ifdef DGSP_SR_GLOBAL_GATHER
+    return false;
+#else
+    return (unsigned long long)p.K * (unsigned long long)p.N * 4ull <= 0xffffffffull;
+#endif
+}
+
+// Dense-row loads in flight per lane of the sequential kernels: enough to fill, not to overflow,
+// the L1 when rows of X are scattered (about 1 KB per wave: 4 / V loads), four when the matrix is
+// known to be banded (neighbouring rows then share their rows of X and mostly hit in cache).
+inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 0.05; }
+
+template <int V, bool XBUF, int DEPTH>
+int launch_rs_sr_v(const Problem& p) {
     const int logG = sr_lanes_log2(p.N, V);
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
@@ -110,23 +125,29 @@ int launch_rs_sr(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
-    switch (V) {
-        case 4: DGSP_LAUNCH(rs_sr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        case 2: DGSP_LAUNCH(rs_sr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        default: DGSP_LAUNCH(rs_sr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-    }
+    DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
+}
+
+int launch_rs_sr(const Problem& p) {
+    const bool xb = x_fits_descriptor(p);
+    switch (vector_width(p.N, p.X, p.Y)) {
+        case 4:
+            if (banded(p)) return xb ? launch_rs_sr_v<4, true, 4>(p) : launch_rs_sr_v<4, false, 4>(p);
+            return xb ? launch_rs_sr_v<4, true, 1>(p) : launch_rs_sr_v<4, false, 1>(p);
+        case 2:
+            if (banded(p)) return xb ? launch_rs_sr_v<2, true, 4>(p) : launch_rs_sr_v<2, false, 4>(p);
+            return xb ? launch_rs_sr_v<2, true, 2>(p) : launch_rs_sr_v<2, false, 2>(p);
+        default: return xb ? launch_rs_sr_v<1, true, 4>(p) : launch_rs_sr_v<1, false, 4>(p);
+    }
 }
 
 // ---------------------------------------------------------------- balanced launches
 // Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: the chunk size the
 // main kernel derives for `parts` chunks rounded to `quantum` items, cut into tiles of `tile` items.
 int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum, unsigned tile) {
-    int logP = ilog2_ceil(p.N);
-    if (logP > 6) logP = 6;
-    const long long threads = (long long)p.M << logP;
-    const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, tile, logP);
+    const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, tile);
     return DGSP_OK;
 }
 
@@ -179,26 +200,31 @@ int launch_nb_pr(const Problem& p) {
     }
 }
 
-template <int V>
+template <int V, bool XBUF, int DEPTH>
 int launch_nb_sr_v(const Problem& p) {
     const int logG = sr_lanes_log2(p.N, V);
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
-    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V>)), col_blocks);
+    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>)), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 1u << logU, kNbSrTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH(nb_sr_kernel<V>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+        DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
 int launch_nb_sr(const Problem& p) {
+    const bool xb = x_fits_descriptor(p);
     switch (vector_width(p.N, p.X, p.Y)) {
-        case 4: return launch_nb_sr_v<4>(p);
-        case 2: return launch_nb_sr_v<2>(p);
-        default: return launch_nb_sr_v<1>(p);
+        case 4:
+            if (banded(p)) return xb ? launch_nb_sr_v<4, true, 4>(p) : launch_nb_sr_v<4, false, 4>(p);
+            return xb ? launch_nb_sr_v<4, true, 1>(p) : launch_nb_sr_v<4, false, 1>(p);
+        case 2:
+            if (banded(p)) return xb ? launch_nb_sr_v<2, true, 4>(p) : launch_nb_sr_v<2, false, 4>(p);
+            return xb ? launch_nb_sr_v<2, true, 2>(p) : launch_nb_sr_v<2, false, 2>(p);
+        default: return xb ? launch_nb_sr_v<1, true, 4>(p) : launch_nb_sr_v<1, false, 4>(p);
     }
 }
 
@@ -214,7 +240,8 @@ dgsp_thresholds_t g_thresholds = {
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
-        const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL) {
+        const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
+        double col_span = 0.0) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
     if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return DGSP_OK;
@@ -226,7 +253,7 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
 
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
-    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase};
+    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span};
     switch (algo) {
         case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
         case DGSP_RS_PR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_pr(p);
@@ -252,10 +279,12 @@ extern "C" int dgsp_spmm_csr_nnz(int64_t M, int64_t K, int64_t N, int64_t nnz, c
 
 extern "C" int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                                    const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
-                                   int phase, void* stream) {
+                                   int phase, const dgsp_features_t* features, void* stream) {
     if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
     if (phase < DGSP_PHASE_ALL || phase > DGSP_PHASE_MAIN) return DGSP_ERR_INVALID_ARG;
-    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase);
+    if (features && nnz < 0) nnz = features->nnz;
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase,
+               features ? features->col_span : 0.0);
 }
 
 extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_features_t* features,
@@ -266,7 +295,7 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
     int algo = (N >= 1) ? dgsp_select_algo(features, N) : DGSP_NB_PR;
     if (algo < 0) return DGSP_ERR_INVALID_ARG;
     if (chosen) *chosen = algo;
-    return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream);
+    return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, features->col_span);
 }
 
 // Section 2.2: N picks the reduction, row-length statistics pick the partition.
@@ -315,6 +344,7 @@ extern "C" int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_
     const double var = (double)num / ((double)M * (double)M);
     f.stdv_row = std::sqrt(var);
     f.cv_row = f.avg_row > 0 ? f.stdv_row / f.avg_row : 0.0;
+    f.col_span = 0.0;
     *out = f;
     return DGSP_OK;
 }
@@ -328,6 +358,35 @@ extern "C" int dgsp_gather_probe(float* out, const float* x, const int32_t* idx,
     hipLaunchKernelGGL(gather_probe_kernel, dim3(kGatherProbeBlocks), dim3(kBlock), 0, (hipStream_t)stream, out, x,
                        idx, (long long)n);
     return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
+}
+
+extern "C" int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,
+                                           dgsp_features_t* out) {
+    const int rc = dgsp_features_from_rowptr_host(M, K, rowptr, out);
+    if (rc != DGSP_OK) return rc;
+    if (out->nnz > 0 && !colidx) return DGSP_ERR_INVALID_ARG;
+    if (M == 0 || K == 0 || out->nnz == 0) return DGSP_OK;
+    // mean over the non-empty rows of (largest - smallest column + 1) / K
+    double sum = 0.0;
+    int64_t rows = 0;
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t s = rowptr[i], e = rowptr[i + 1];
+        if (s == e) continue;
+        int32_t lo = colidx[s], hi = colidx[s];
+        if (colidx[e - 1] < lo || e - s <= 2) {
+            for (int64_t p = s; p < e; ++p) { lo = colidx[p] < lo ? colidx[p] : lo; hi = colidx[p] > hi ? colidx[p] : hi; }
+        } else {
+            // sorted rows (the usual case) need only their two ends; verify cheaply, else scan
+            bool sorted = true;
+            for (int64_t p = s + 1; p < e; ++p) if (colidx[p] < colidx[p - 1]) { sorted = false; break; }
+            if (sorted) hi = colidx[e - 1];
+            else for (int64_t p = s; p < e; ++p) { lo = colidx[p] < lo ? colidx[p] : lo; hi = colidx[p] > hi ? colidx[p] : hi; }
+        }
+        sum += (double)(hi - lo + 1) / (double)K;
+        ++rows;
+    }
+    out->col_span = rows ? sum / (double)rows : 0.0;
+    return DGSP_OK;
 }
 
 extern "C" int dgsp_copy_f32(float* dst, const float* src, int64_t n, void* stream) {

@@ -94,6 +94,72 @@ __device__ __forceinline__ int stream_load(const int* p) { return __builtin_nont
 __device__ __forceinline__ float stream_load(const float* p) { return __builtin_nontemporal_load(p); }
 
 // ---------------------------------------------------------------------------
+// range-checked buffer accesses
+// ---------------------------------------------------------------------------
+//
+// A buffer descriptor carries a base and a size; a lane whose byte offset falls
+// outside reads zeros / writes nothing and causes no memory traffic.  That is
+// predication without a branch: the instruction is always issued, so the
+// outstanding-operation counter can be waited on exactly and later loads can
+// stay in flight across it.  kOutOfRange switches a lane off.
+
+#ifndef DGSP_GATHER_AUX
+#define DGSP_GATHER_AUX 0   // cache-policy bits of the dense-operand gather
+#endif
+constexpr unsigned kBufferFlags = 0x00020000u;      // raw 32-bit buffer descriptor, dword 3
+constexpr unsigned kOutOfRange = 0xffffffffu;
+
+// Descriptor for `bytes` bytes starting at p (clamped to the 4 GB a descriptor can span).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, unsigned long long bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0,
+                                             bytes > 0xffffffffull ? 0xffffffffu : (unsigned)bytes, kBufferFlags);
+}
+
+// Loads V consecutive floats at byte_offset; lanes whose offset is out of range get zeros and
+// cause no memory traffic.  `aux` 2 marks the load non-temporal.
+template <int V>
+__device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V]) {
+    if constexpr (V == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    } else if constexpr (V == 2) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+        x[0] = t.x; x[1] = t.y;
+    } else {
+        x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
+    if constexpr (V == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const f4 t = {x[0], x[1], x[2], x[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
+    } else if constexpr (V == 2) {
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const f2 t = {x[0], x[1]};
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, 0);
+    }
+}
+
+// Column index / value streams: non-temporal dword loads through a descriptor.
+__device__ __forceinline__ int buffer_stream_i32(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(r, byte_offset, 0, 2);
+}
+__device__ __forceinline__ float buffer_stream_f32(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_offset, 0, 2));
+}
+
+// ---------------------------------------------------------------------------
 // wave64 segmented inclusive scan on DPP (vectorized segment reduction,
 // paper Section 2.1.1)
 // ---------------------------------------------------------------------------

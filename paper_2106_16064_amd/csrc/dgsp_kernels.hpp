@@ -133,13 +133,14 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* 
 // blockIdx.y selects the column block when N > 64*V.
 
 constexpr int kRsSrTile = 512;   // cached pairs per wave and round
-#ifndef DGSP_SR_DEPTH
-#define DGSP_SR_DEPTH 4
-#endif
-constexpr int kSrDepth = DGSP_SR_DEPTH;   // dense-row loads a lane keeps in flight in the sequential kernels
+// DEPTH (template parameter of the sequential kernels) = dense-row loads a lane keeps in flight.
+// More is not better: a wave's load of 64 x 16 bytes is 1 KB, and once the loads in flight on a
+// CU exceed what its L1 can hold the misses stall each other (measured: rows of random columns,
+// N = 32, 182 us at depth 1, 266 us at depth 4); rows that hit in cache want the latency hidden
+// instead (27-point stencil, N = 8: 204 us at depth 4, 260 us at depth 1).  The host picks.
 
-template <int V>
-__global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* __restrict__ rowptr,
+template <int V, bool XBUF, int DEPTH>
+__global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -163,6 +164,11 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wib;
     const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;
 
+    // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
+    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? x_bytes : 0ull);
+    const unsigned n_bytes = (unsigned)n * 4u;
+
     for (unsigned rg = gw; rg < ngroups; rg += nwaves) {
         const long long row0 = (long long)rg * rows_per_wave;
         const long long row = row0 + g;
@@ -178,32 +184,40 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, int N, const int* 
 
         for (unsigned ws = ps; ws < pe; ws += (unsigned)T) {
             wave_lds_sync();                    // last round's readers are done
+            const unsigned long long bytes = (unsigned long long)(pe - ws) * 4ull;
+            const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + ws, bytes);
+            const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + ws, bytes);
 #pragma unroll
             for (int k = 0; k < T / kWave; ++k) {
-                const unsigned p = ws + (unsigned)(k * kWave + lane);
-                if (p < pe) { cc[k * kWave + lane] = stream_load(colidx + p); cv[k * kWave + lane] = stream_load(vals + p); }
+                if (ws + (unsigned)(k * kWave) < pe) {       // wave-uniform
+                    const unsigned off = (unsigned)(k * kWave + lane) * 4u;
+                    cc[k * kWave + lane] = buffer_stream_i32(rc, off);
+                    cv[k * kWave + lane] = buffer_stream_f32(ra, off);
+                }
             }
             wave_lds_sync();
             const unsigned we = pe - ws > (unsigned)T ? ws + T : pe;
             const unsigned lo = rs > ws ? rs : ws;
             const unsigned hi = re < we ? re : we;
             if (col_ok) {
-                for (unsigned p0 = lo; p0 < hi; p0 += kSrDepth) {
-                    float x[kSrDepth][V]; float a[kSrDepth];
+                for (unsigned p0 = lo; p0 < hi; p0 += DEPTH) {
+                    float x[DEPTH][V]; float a[DEPTH];
 #pragma unroll
-                    for (int u = 0; u < kSrDepth; ++u) {
-                        if (p0 + u < hi) {
-                            const int e = (int)(p0 + u - ws);
-                            a[u] = cv[e];
-                            load_vec<V>(X + (size_t)cc[e] * N + n, x[u]);
+                    for (int u = 0; u < DEPTH; ++u) {
+                        const bool ok = p0 + u < hi;
+                        const int e = ok ? (int)(p0 + u - ws) : 0;
+                        a[u] = ok ? cv[e] : 0.0f;
+                        const unsigned c = (unsigned)cc[e];
+                        if constexpr (XBUF) {
+                            buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + n_bytes : kOutOfRange, x[u]);
                         } else {
-                            a[u] = 0.0f;
+                            load_vec<V>(X + (size_t)(ok ? c : 0u) * N + n, x[u]);
 #pragma unroll
-                            for (int i = 0; i < V; ++i) x[u][i] = 0.0f;
+                            for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
                         }
                     }
 #pragma unroll
-                    for (int u = 0; u < kSrDepth; ++u)
+                    for (int u = 0; u < DEPTH; ++u)
 #pragma unroll
                         for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);
                 }
@@ -258,15 +272,16 @@ __device__ __forceinline__ unsigned merge_chunk_items(unsigned items, unsigned p
 // unit > 0: pieces are the multiples of `unit` items.  unit == 0: pieces are
 // the chunks for `parts` chunks (see merge_chunk_items), cut further into
 // tiles of `tile` items counted from the chunk's start when tile > 0.
-// 2^logP consecutive threads share a row.
+// One thread per row: split rows are few (at most two per piece), the test is
+// the cost.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
-                                                             unsigned quantum, unsigned tile, int logP) {
-    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
-    const long long row = t >> logP;
+                                                             unsigned quantum, unsigned tile) {
+    const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (row >= M) return;
     const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
     const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
+    if (first == last) return;                                           // an empty row is a single item
     if (unit != 0) {
         if (first / unit == last / unit) return;
     } else {
@@ -275,7 +290,7 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const 
         if (c1 == c2 && (tile == 0 || (first - c1 * per) / tile == (last - c1 * per) / tile)) return;
     }
     float* y = Y + (size_t)row * N;
-    for (int n = (int)(t & ((1 << logP) - 1)); n < N; n += 1 << logP) y[n] = 0.0f;
+    for (int n = 0; n < N; ++n) y[n] = 0.0f;
 }
 
 // The chunks of the calling wave: chunk(s) = s * nwaves + wave id, s < kSubRanges.
@@ -362,51 +377,6 @@ constexpr unsigned kNoRow = 0xffffffffu;
 // tile's loads stay in flight while this tile is reduced.
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
-constexpr unsigned kBufferFlags = 0x00020000u;      // raw 32-bit buffer descriptor, dword 3
-constexpr unsigned kOutOfRange = 0xffffffffu;
-
-// Descriptor for `bytes` bytes starting at p (clamped to the 4 GB a descriptor can span).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, unsigned long long bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0,
-                                             bytes > 0xffffffffull ? 0xffffffffu : (unsigned)bytes, kBufferFlags);
-}
-
-// Loads V consecutive floats at byte_offset; lanes whose offset is out of range get zeros and
-// cause no memory traffic.  `aux` 2 marks the load non-temporal.
-template <int V>
-__device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V]) {
-    if constexpr (V == 4) {
-        typedef float f4 __attribute__((ext_vector_type(4)));
-        typedef unsigned u4 __attribute__((ext_vector_type(4)));
-        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
-        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-    } else if constexpr (V == 2) {
-        typedef float f2 __attribute__((ext_vector_type(2)));
-        typedef unsigned u2 __attribute__((ext_vector_type(2)));
-        const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, 0));
-        x[0] = t.x; x[1] = t.y;
-    } else {
-        x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, 0));
-    }
-}
-
-template <int V>
-__device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
-    if constexpr (V == 4) {
-        typedef float f4 __attribute__((ext_vector_type(4)));
-        typedef unsigned u4 __attribute__((ext_vector_type(4)));
-        const f4 t = {x[0], x[1], x[2], x[3]};
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
-    } else if constexpr (V == 2) {
-        typedef float f2 __attribute__((ext_vector_type(2)));
-        typedef unsigned u2 __attribute__((ext_vector_type(2)));
-        const f2 t = {x[0], x[1]};
-        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, 0);
-    } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, 0);
-    }
-}
-
 template <int V, int KQ>
 __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
@@ -468,7 +438,11 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     };
     // the dense operand: byte offsets of X rows fit 32 bits unless X is 4 GB or more
     const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+#ifdef DGSP_PR_GLOBAL_GATHER
+    const bool x_small = false;
+#else
     const bool x_small = x_bytes <= 0xffffffffull;
+#endif
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
 
     float carry[V];      // running sum of the row that is open at the tile boundary (wave-uniform)
@@ -669,8 +643,8 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 constexpr int kNbSrTile = 512;
 constexpr int kNbSrLogTile = 9;
 
-template <int V>
-__global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* __restrict__ rowptr,
+template <int V, bool XBUF, int DEPTH>
+__global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -703,6 +677,10 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
 
     const ChunkPlan plan = plan_chunks(rowptr, M, U);     // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
+    // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
+    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? x_bytes : 0ull);
+    const unsigned n_bytes = (unsigned)n * 4u;
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
     unsigned d0, d1;
@@ -714,11 +692,16 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
 
         wave_lds_sync();                        // previous tile's readers are done
         // entries: at most W, the exact count follows from the row ends
+        {
+            const unsigned long long bytes = (unsigned long long)(nnz - js) * 4ull;
+            const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + js, bytes);
+            const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + js, bytes);
 #pragma unroll
-        for (int k = 0; k < W / kWave; ++k) {
-            const int e = k * kWave + lane;
-            const unsigned p = js + (unsigned)e;
-            if (p < nnz) { cc[e] = stream_load(colidx + p); cv[e] = stream_load(vals + p); }
+            for (int k = 0; k < W / kWave; ++k) {
+                const int e = k * kWave + lane;
+                cc[e] = buffer_stream_i32(rc, (unsigned)e * 4u);
+                cv[e] = buffer_stream_f32(ra, (unsigned)e * 4u);
+            }
         }
         // slots for the rows that cross run boundaries inside the tile
 #pragma unroll
@@ -787,23 +770,24 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, int N, const int* 
                 }
             };
 
-            for (unsigned p0 = j; p0 < j_end; p0 += kSrDepth) {
-                float x[kSrDepth][V]; float a[kSrDepth];
+            for (unsigned p0 = j; p0 < j_end; p0 += DEPTH) {
+                float x[DEPTH][V]; float a[DEPTH];
 #pragma unroll
-                for (int u = 0; u < kSrDepth; ++u) {
-                    const unsigned p = p0 + u;
-                    if (p < j_end) {
-                        const int e = (int)(p - js);
-                        a[u] = cv[e];
-                        load_vec<V>(X + (size_t)cc[e] * N + n, x[u]);
+                for (int u = 0; u < DEPTH; ++u) {
+                    const bool ok = p0 + u < j_end;
+                    const int e = ok ? (int)(p0 + u - js) : 0;
+                    a[u] = ok ? cv[e] : 0.0f;
+                    const unsigned c = (unsigned)cc[e];
+                    if constexpr (XBUF) {
+                        buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + n_bytes : kOutOfRange, x[u]);
                     } else {
-                        a[u] = 0.0f;
+                        load_vec<V>(X + (size_t)(ok ? c : 0u) * N + n, x[u]);
 #pragma unroll
-                        for (int i = 0; i < V; ++i) x[u][i] = 0.0f;
+                        for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < kSrDepth; ++u) {
+                for (int u = 0; u < DEPTH; ++u) {
                     const unsigned p = p0 + u;
                     if (p < j_end) {
                         flush_rows_ending_at(p);             // rows that end before entry p

@@ -286,9 +286,9 @@ def test_phase_entry_point_equals_the_whole_call(dg):
         assert ok, (ALGO_NAMES[algo], worst)
     L = dg.lib()
     assert L.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(),
-                                 dX.data_ptr(), dY.data_ptr(), -1, 0, None) == dg.ERR_INVALID_ARG
+                                 dX.data_ptr(), dY.data_ptr(), -1, 0, None, None) == dg.ERR_INVALID_ARG
     assert L.dgsp_spmm_csr_phase(A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(),
-                                 dX.data_ptr(), dY.data_ptr(), 0, 5, None) == dg.ERR_INVALID_ARG
+                                 dX.data_ptr(), dY.data_ptr(), 0, 5, None, None) == dg.ERR_INVALID_ARG
 
 
 def test_gather_probe_sums_every_gathered_value(dg):
@@ -300,3 +300,21 @@ def test_gather_probe_sums_every_gathered_value(dg):
     dg.dgsp_gather_probe(out, x, idx)
     torch.cuda.synchronize()
     assert out.double().sum().item() == x[idx.long()].double().sum().item()
+
+
+@pytest.mark.parametrize("N", [1, 2, 6, 8, 64])
+def test_column_span_hint_changes_nothing_but_speed(dg, N):
+    """With a matrix's features (banded: small col_span) the sequential kernels keep more loads in flight."""
+    import torch
+    A = wl.stencil27_csr(48, seed=3)
+    X = wl.dense_matrix(A.K, N, "uniform", seed=N)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    dA = dg.DeviceCsr(A)
+    assert 0 < dA.features.col_span <= 0.05
+    dX = torch.from_numpy(X).cuda()
+    for algo in range(4):
+        dY = torch.full((A.M, N), float("nan"), device="cuda:0")
+        dA.spmm(dX, algo=algo, Y=dY)          # passes the features along with the named kernel
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+        assert ok, (ALGO_NAMES[algo], N, worst)

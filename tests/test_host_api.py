@@ -108,3 +108,26 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(dg, "LIB_PATH", tmp_path / "libdgsp.so")
     with pytest.raises(dg.DgspError):
         dg.lib()
+
+
+def test_column_span_feature():
+    S = wl.stencil27_csr(10)
+    f = dg.dgsp_features_from_csr_host(S.M, S.K, S.rowptr, S.colidx)
+    # interior rows span 2*(n*n + n + 1) + 1 columns of n^3
+    assert 0.1 < f.col_span < 2 * (100 + 10 + 1 + 1) / 1000
+    assert (f.nnz, f.max_row) == (S.nnz, 27)
+    R = wl.poisson_csr(2000, 2000, 16.0, seed=1)
+    fr = dg.dgsp_features_from_csr_host(R.M, R.K, R.rowptr, R.colidx)
+    assert fr.col_span > 0.7
+    # unsorted rows give the same span
+    rng = np.random.default_rng(0)
+    c2 = R.colidx.copy()
+    for i in range(R.M):
+        s, e = R.rowptr[i], R.rowptr[i + 1]
+        c2[s:e] = rng.permutation(c2[s:e])
+    fu = dg.dgsp_features_from_csr_host(R.M, R.K, R.rowptr, c2)
+    assert fu.col_span == pytest.approx(fr.col_span, rel=1e-12)
+    # by hand: rows {1,3}, {}, {5} of K = 10 -> ((3-1+1) + 1) / 2 / 10
+    f3 = dg.dgsp_features_from_csr_host(3, 10, np.array([0, 2, 2, 3], np.int32), np.array([1, 3, 5], np.int32))
+    assert f3.col_span == pytest.approx(0.2)
+    assert dg.dgsp_features_from_rowptr_host(3, 10, np.array([0, 2, 2, 3], np.int32)).col_span == 0.0
