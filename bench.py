@@ -17,6 +17,7 @@ prints one JSON line and writes details under gpurun_out/):
     --suite configs   every kernel on the R-MAT and stencil configurations
     --suite sweep     the 24-matrix x 10-N selector sweep (loss vs best kernel)
     --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
+    --suite fit       fits the selector thresholds on a finished sweep (no GPU)
 """
 from __future__ import annotations
 
@@ -320,6 +321,46 @@ def run_sweep(args):
     return 0
 
 
+def run_fit(args):
+    """Grid-fits the selector thresholds on the seed-0 matrices of a finished sweep
+    (gpurun_out/bench_sweep.jsonl), checks them on the seed-1 matrices.  No GPU needed."""
+    path = args.out or os.path.join("gpurun_out", "bench_sweep.jsonl")
+    rows = [json.loads(l) for l in open(path)]
+    for r in rows:
+        r["stdv"] = r["avg_row"] * r["cv_row"]
+
+    def choose(r, t):
+        npm, pr_avg, pr_cv, sr_cv, sr_std = t
+        if r["N"] <= npm:
+            return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv) else "nb_pr"
+        return "nb_sr" if (r["cv_row"] > sr_cv and r["stdv"] > sr_std) else "rs_sr"
+
+    def loss(rs, t):
+        l = [r["ms"][choose(r, t)] / min(r["ms"].values()) - 1 for r in rs]
+        return sum(l) / len(l), max(l)
+
+    fit = [r for r in rows if r["matrix"].endswith("_s0")]
+    test = [r for r in rows if r["matrix"].endswith("_s1")]
+    grid = [(npm, a, c, sc, ss) for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
+            for c in (0.3, 1.0, 2.0, 4.0, 1e30) for sc in (0.3, 0.8, 1.0, 1.5, 2.0, 3.5, 1e9) for ss in (0, 3, 10, 30, 60)]
+    best = min(grid, key=lambda t: loss(fit, t)[0])
+    paper = min((t for t in grid if t[0] == 4 and t[2] == 1e30 and t[4] == 0), key=lambda t: loss(fit, t)[0])
+    single = {k: (sum(r["ms"][k] / min(r["ms"].values()) - 1 for r in rows) / len(rows)) for k in rows[0]["ms"]}
+    per_n = {}
+    for r in rows:
+        per_n.setdefault(r["N"], []).append(r["ms"][choose(r, best)] / min(r["ms"].values()) - 1)
+    print(json.dumps({
+        "suite": "fit", "cells": len(rows),
+        "thresholds": dict(zip(("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min"), best)),
+        "mean_loss_fit_seed0": loss(fit, best)[0], "mean_loss_heldout_seed1": loss(test, best)[0],
+        "mean_loss_all": loss(rows, best)[0], "max_loss_all": loss(rows, best)[1],
+        "paper_shaped_tree": {"thresholds": paper, "mean_loss_fit": loss(fit, paper)[0],
+                              "mean_loss_heldout": loss(test, paper)[0]},
+        "always_one_kernel_mean_loss": single,
+        "mean_loss_per_N": {str(n): sum(v) / len(v) for n, v in sorted(per_n.items())}}))
+    return 0
+
+
 def run_kernel(args):
     """One kernel in a plain loop, for rocprofv3."""
     import torch
@@ -345,7 +386,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "kernel"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "kernel", "fit"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -355,6 +396,8 @@ def main():
     ap.add_argument("--sweep-m", type=int, default=1 << 18)
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
+    if args.suite == "fit":
+        return run_fit(args)
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
         return 2

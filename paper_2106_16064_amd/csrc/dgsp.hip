@@ -76,9 +76,34 @@ struct Problem {
         if (hipGetLastError() != hipSuccess) return DGSP_ERR_LAUNCH;                          \
     } while (0)
 
+// ---------------------------------------------------------------- launch geometry helpers
+// Workgroups of `kernel` that one CU keeps resident (registers and LDS decide).  The balanced
+// kernels cut the work into equal shares per wave, so their grid must not exceed what runs at
+// once: a workgroup that waits for a slot would start its share when the others are done.
+template <typename K>
+int resident_blocks_per_cu(K kernel) {
+    static std::mutex mu;
+    static std::map<std::pair<const void*, int>, int> cache;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 4;
+    const auto key = std::make_pair(reinterpret_cast<const void*>(kernel), dev);
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n <= 0) n = 4;
+    cache[key] = n;
+    return n;
+}
+
 // ---------------------------------------------------------------- row-split launches
-int launch_rs_pr(const Problem& p) {
-    const int V = vector_width(p.N, p.X, p.Y);
+// X can be addressed with 32-bit byte offsets (through a buffer descriptor)
+inline bool x_fits_descriptor(const Problem& p) {
+    return (unsigned long long)p.K * (unsigned long long)p.N * 4ull <= 0xffffffffull;
+}
+
+template <int V, bool XBUF>
+int launch_rs_pr_v(const Problem& p) {
     const int logG = p.nnz >= 0 ? pr_lanes_log2(p.nnz, p.M) : -1;
     // one wave per row group when lanes-per-row is known; else assume the
     // finest split the kernel may choose (2 lanes per row) and let waves stride
@@ -86,12 +111,17 @@ int launch_rs_pr(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));
-    switch (V) {
-        case 4: DGSP_LAUNCH(rs_pr_kernel<4>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        case 2: DGSP_LAUNCH(rs_pr_kernel<2>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-        default: DGSP_LAUNCH(rs_pr_kernel<1>, grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG); break;
-    }
+    DGSP_LAUNCH((rs_pr_kernel<V, XBUF>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
+}
+
+int launch_rs_pr(const Problem& p) {
+    const bool xb = x_fits_descriptor(p);
+    switch (vector_width(p.N, p.X, p.Y)) {
+        case 4: return xb ? launch_rs_pr_v<4, true>(p) : launch_rs_pr_v<4, false>(p);
+        case 2: return xb ? launch_rs_pr_v<2, true>(p) : launch_rs_pr_v<2, false>(p);
+        default: return xb ? launch_rs_pr_v<1, true>(p) : launch_rs_pr_v<1, false>(p);
+    }
 }
 
 // lanes per row of the sequential kernels: enough lanes of width V to span N, at most a wave
@@ -99,15 +129,6 @@ inline int sr_lanes_log2(long long N, int V) {
     const long long need = (N + V - 1) / V;
     const int lg = ilog2_ceil(need);
     return lg > 6 ? 6 : lg;
-}
-
-// X can be addressed with 32-bit byte offsets (through a buffer descriptor)
-inline bool x_fits_descriptor(const Problem& p) {
-#ifdef DGSP_SR_GLOBAL_GATHER
-    return false;
-#else
-    return (unsigned long long)p.K * (unsigned long long)p.N * 4ull <= 0xffffffffull;
-#endif
 }
 
 // Dense-row loads in flight per lane of the sequential kernels: enough to fill, not to overflow,
@@ -149,25 +170,6 @@ int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned qua
     const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
     DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, tile);
     return DGSP_OK;
-}
-
-// Workgroups of `kernel` that one CU keeps resident (registers and LDS decide).  The balanced
-// kernels cut the work into equal shares per wave, so their grid must not exceed what runs at
-// once: a workgroup that waits for a slot would start its share when the others are done.
-template <typename K>
-int resident_blocks_per_cu(K kernel) {
-    static std::mutex mu;
-    static std::map<std::pair<const void*, int>, int> cache;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 4;
-    const auto key = std::make_pair(reinterpret_cast<const void*>(kernel), dev);
-    std::lock_guard<std::mutex> lock(mu);
-    auto it = cache.find(key);
-    if (it != cache.end()) return it->second;
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n <= 0) n = 4;
-    cache[key] = n;
-    return n;
 }
 
 // blocks of a machine-filling grid that shares nnz + M merge-path items in chunks of `chunk`
@@ -234,9 +236,9 @@ int launch_nb_sr(const Problem& p) {
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
     /* pr_avg_row_min  */ 0.0,
-    /* pr_cv_max       */ 4.0,
+    /* pr_cv_max       */ 1.0,
     /* sr_cv_min       */ 0.3,
-    /* sr_stdv_min     */ 30.0,
+    /* sr_stdv_min     */ 3.0,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,

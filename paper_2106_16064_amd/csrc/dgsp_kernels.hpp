@@ -39,71 +39,90 @@ __host__ __device__ __forceinline__ int pr_lanes_log2(long long nnz, long long M
 
 constexpr int kRsPrUnroll = 4;   // row groups a wave keeps in flight
 
-template <int V>
-__global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* __restrict__ rowptr,
+template <int V, bool XBUF>
+__global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG_in) {
     constexpr int U = kRsPrUnroll;
     const int lane = lane_id();
-    const int logG = logG_in >= 0 ? logG_in : pr_lanes_log2(rowptr[M], M);
+    const unsigned nnz = (unsigned)rowptr[M];
+    const int logG = logG_in >= 0 ? logG_in : pr_lanes_log2(nnz, M);
     const int G = 1 << logG;
     const int gl = lane & (G - 1);              // lane inside the group
-    const int rows_per_wave = kWave >> logG;
+    const int g = lane >> logG;                 // group inside the wave
+    const int rows_per_wave = kWave >> logG;    // at most 32: a row has at least two lanes
     const unsigned nwaves = gridDim.x * kWavesPerBlock;
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
     // a wave step covers U * rows_per_wave consecutive rows: U independent load -> gather -> reduce chains
     const unsigned rows_per_step = (unsigned)(U * rows_per_wave);
     const unsigned nsteps = ((unsigned)M + rows_per_step - 1) / rows_per_step;
+    // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? (unsigned long long)K * (unsigned)N * 4ull : 0ull);
+
+    auto fetch_dense = [&](unsigned c, bool ok, int n0, float (&x)[V]) {
+        if constexpr (XBUF) {
+            buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + (unsigned)n0 * 4u : kOutOfRange, x);
+        } else {
+            load_vec<V>(X + (size_t)c * N + n0, x);                      // c is 0 when switched off: a valid row
+#pragma unroll
+            for (int i = 0; i < V; ++i) x[i] = ok ? x[i] : 0.0f;
+        }
+    };
 
     for (int n0 = 0; n0 < N; n0 += V) {
         for (unsigned st = gw; st < nsteps; st += nwaves) {
-            long long row[U]; unsigned rs[U], re[U];
+            // Row bounds: lanes 0..rows_per_wave fetch consecutive rowptr entries with one coalesced
+            // load per row group and every lane picks its row's pair from them (cross-lane read).
+            // Letting all lanes of a group load the same two words costs the memory pipeline a
+            // cycle per lane, as much as the gather itself.
+            unsigned rs[U], re[U];
+            const unsigned long long row0 = (unsigned long long)st * rows_per_step;
+            const __amdgpu_buffer_rsrc_t rp = make_buffer(rowptr + row0, ((unsigned long long)M + 1 - row0) * 4ull);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                row[u] = (long long)st * rows_per_step + u * rows_per_wave + (lane >> logG);
-                rs[u] = 0; re[u] = 0;
-                if (row[u] < M) { rs[u] = (unsigned)rowptr[row[u]]; re[u] = (unsigned)rowptr[row[u] + 1]; }
+                const unsigned idx = (unsigned)(u * rows_per_wave + lane);
+                const unsigned v = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(
+                    rp, lane <= rows_per_wave ? idx * 4u : kOutOfRange, 0, 0);     // past rowptr[M]: 0
+                rs[u] = (unsigned)__shfl((int)v, g);
+                re[u] = (unsigned)__shfl((int)v, g + 1);
+                if (row0 + (unsigned)(u * rows_per_wave + g) >= (unsigned long long)M) re[u] = rs[u];   // no such row
             }
+            // the step's entries start at its first row's start: offsets from there stay small
+            const unsigned base = (unsigned)uniform((int)rs[0]);
+            const unsigned long long bytes = (unsigned long long)(nnz - (base < nnz ? base : nnz)) * 4ull;
+            const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + base, bytes);
+            const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + base, bytes);
+            // column and value of the entry at position p (zeros when switched off)
+            auto fetch_entry = [&](unsigned p, bool ok, unsigned& c, float& a) {
+                const unsigned off = ok ? (p - base) * 4u : kOutOfRange;
+                c = (unsigned)buffer_stream_i32(rc, off);
+                a = buffer_stream_f32(ra, off);
+            };
             float acc[U][V];
-            int c[U]; float a[U];
             // first entry of every lane: for rows no longer than the group this is all there is
+            {
+                unsigned c[U]; float a[U], x[U][V];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const unsigned p = rs[u] + gl;
-                const bool ok = p < re[u];
-                c[u] = ok ? stream_load(colidx + p) : -1;
-                a[u] = ok ? stream_load(vals + p) : 0.0f;
-            }
+                for (int u = 0; u < U; ++u) fetch_entry(rs[u] + gl, rs[u] + gl < re[u], c[u], a[u]);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float x[V];
-                if (c[u] >= 0) load_vec<V>(X + (size_t)c[u] * N + n0, x);
-                else {
+                for (int u = 0; u < U; ++u) fetch_dense(c[u], rs[u] + gl < re[u], n0, x[u]);
 #pragma unroll
-                    for (int i = 0; i < V; ++i) x[i] = 0.0f;
-                }
+                for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int i = 0; i < V; ++i) acc[u][i] = a[u] * x[i];
+                    for (int i = 0; i < V; ++i) acc[u][i] = a[u] * x[u][i];
             }
             // the rest of longer rows, two gathers in flight per lane
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 for (unsigned p = rs[u] + gl + G; p < re[u]; p += 2u * G) {
-                    const unsigned q = p + G;
-                    const bool ok2 = q < re[u];
-                    const int c0 = stream_load(colidx + p);
-                    const float a0 = stream_load(vals + p);
-                    const int c1 = ok2 ? stream_load(colidx + q) : -1;
-                    const float a1 = ok2 ? stream_load(vals + q) : 0.0f;
-                    float x0[V], x1[V];
-                    load_vec<V>(X + (size_t)c0 * N + n0, x0);
-                    if (c1 >= 0) load_vec<V>(X + (size_t)c1 * N + n0, x1);
-                    else {
-#pragma unroll
-                        for (int i = 0; i < V; ++i) x1[i] = 0.0f;
-                    }
+                    unsigned c0, c1; float a0, a1, x0[V], x1[V];
+                    const bool ok1 = p + G < re[u];
+                    fetch_entry(p, true, c0, a0);
+                    fetch_entry(p + G, ok1, c1, a1);
+                    fetch_dense(c0, true, n0, x0);
+                    fetch_dense(c1, ok1, n0, x1);
 #pragma unroll
                     for (int i = 0; i < V; ++i) acc[u][i] = fmaf(a1, x1[i], fmaf(a0, x0[i], acc[u][i]));
                 }
@@ -111,7 +130,8 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, int N, const int* 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 segmented_scan<V>(acc[u], gl, lane, G);   // all 64 lanes arrive here together
-                if (row[u] < M && gl == G - 1) store_vec<V>(Y + (size_t)row[u] * N + n0, acc[u]);
+                const unsigned long long row = row0 + (unsigned)(u * rows_per_wave + g);
+                if (row < (unsigned long long)M && gl == G - 1) store_vec<V>(Y + (size_t)row * N + n0, acc[u]);
             }
         }
     }
