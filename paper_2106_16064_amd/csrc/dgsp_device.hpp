@@ -103,9 +103,6 @@ __device__ __forceinline__ float stream_load(const float* p) { return __builtin_
 // outstanding-operation counter can be waited on exactly and later loads can
 // stay in flight across it.  kOutOfRange switches a lane off.
 
-#ifndef DGSP_GATHER_AUX
-#define DGSP_GATHER_AUX 0   // cache-policy bits of the dense-operand gather
-#endif
 constexpr unsigned kBufferFlags = 0x00020000u;      // raw 32-bit buffer descriptor, dword 3
 constexpr unsigned kOutOfRange = 0xffffffffu;
 
@@ -122,15 +119,15 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
     if constexpr (V == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
-        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
     } else if constexpr (V == 2) {
         typedef float f2 __attribute__((ext_vector_type(2)));
         typedef unsigned u2 __attribute__((ext_vector_type(2)));
-        const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+        const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, 0));
         x[0] = t.x; x[1] = t.y;
     } else {
-        x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, DGSP_GATHER_AUX));
+        x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, 0));
     }
 }
 

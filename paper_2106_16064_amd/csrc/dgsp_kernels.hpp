@@ -458,11 +458,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     };
     // the dense operand: byte offsets of X rows fit 32 bits unless X is 4 GB or more
     const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
-#ifdef DGSP_PR_GLOBAL_GATHER
-    const bool x_small = false;
-#else
     const bool x_small = x_bytes <= 0xffffffffull;
-#endif
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
 
     float carry[V];      // running sum of the row that is open at the tile boundary (wave-uniform)
