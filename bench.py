@@ -17,6 +17,7 @@ prints one JSON line and writes details under gpurun_out/):
     --suite configs   every kernel on the R-MAT and stencil configurations
     --suite sweep     the 24-matrix x 10-N selector sweep (loss vs best kernel)
     --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
+    --suite size      all four kernels on banded and random matrices of growing size, N <= 8
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
 """
 from __future__ import annotations
@@ -321,6 +322,37 @@ def run_sweep(args):
     return 0
 
 
+def run_size(args):
+    """All four kernels on banded and random matrices of growing size at small N: where the
+    second launch of the balanced kernels starts to pay (fits the selector's pr_nnz_max)."""
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs("gpurun_out", exist_ok=True)
+    path = os.path.join("gpurun_out", args.out or "bench_size.jsonl")
+    gens = [(f"stencil27_n{n}", lambda n=n: wl.stencil27_csr(n, seed=0)) for n in (40, 64, 96, 128)]
+    gens += [(f"fixed27_M2^{lg}", lambda lg=lg: wl.sweep_csr(1 << lg, 27, "fixed", 0)) for lg in (18, 19, 20, 21)]
+    gens += [(f"poisson16_M2^{lg}", lambda lg=lg: wl.sweep_csr(1 << lg, 16, "poisson", 0)) for lg in (18, 20)]
+    cells = 0
+    with open(path, "w") as fh:
+        for name, gen in gens:
+            A = gen()
+            for n in (1, 2, 4, 8):
+                rot = Rotation(A, wl.dense_matrix(A.K, n, "uniform", seed=0))
+                table = variant_table(rot, args.steps, args.warmup)
+                f = rot.mats[0].features
+                sel = dg.dgsp_algo_name(dg.dgsp_select_algo(f, n))
+                best = min(table, key=table.get)
+                fh.write(json.dumps({"matrix": name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row,
+                                     "max_row": f.max_row, "nnz": A.nnz, "ms": table, "selected": sel,
+                                     "best": best, "loss": table[sel] / table[best] - 1.0}) + "\n")
+                fh.flush()
+                cells += 1
+                del rot
+            print(f"[size] {name} done", file=sys.stderr, flush=True)
+    print(json.dumps({"suite": "size", "cells": cells, "file": path}))
+    return 0
+
+
 def run_fit(args):
     """Grid-fits the selector thresholds on the seed-0 matrices of a finished sweep
     (gpurun_out/bench_sweep.jsonl), checks them on the seed-1 matrices.  No GPU needed."""
@@ -329,10 +361,10 @@ def run_fit(args):
     for r in rows:
         r["stdv"] = r["avg_row"] * r["cv_row"]
 
-    def choose(r, t):
+    def choose(r, t, nnz_max=float("inf")):
         npm, pr_avg, pr_cv, sr_cv, sr_std = t
         if r["N"] <= npm:
-            return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv) else "nb_pr"
+            return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv and r["nnz"] < nnz_max) else "nb_pr"
         return "nb_sr" if (r["cv_row"] > sr_cv and r["stdv"] > sr_std) else "rs_sr"
 
     def loss(rs, t):
@@ -349,8 +381,26 @@ def run_fit(args):
     per_n = {}
     for r in rows:
         per_n.setdefault(r["N"], []).append(r["ms"][choose(r, best)] / min(r["ms"].values()) - 1)
+    # the size guard of the parallel side: fitted on the larger matrices of `--suite size`, if that ran
+    size_fit = None
+    size_path = os.path.join(os.path.dirname(path) or ".", "bench_size.jsonl")
+    if os.path.exists(size_path):
+        big = [json.loads(l) for l in open(size_path)]
+        for r in big:
+            r["stdv"] = r["avg_row"] * r["cv_row"]
+
+        def size_loss(rs, nnz_max):
+            l = [r["ms"][choose(r, best, nnz_max)] / min(r["ms"].values()) - 1 for r in rs]
+            return sum(l) / len(l), max(l)
+
+        cands = (5e6, 1e7, 1.5e7, 2e7, 3e7, 4e7, float("inf"))
+        nm = min(cands, key=lambda c: size_loss(big + fit, c)[0])
+        size_fit = {"pr_nnz_max": nm, "cells": len(big),
+                    "mean_loss_size_cells": {str(c): size_loss(big, c)[0] for c in cands},
+                    "max_loss_size_cells": {str(c): size_loss(big, c)[1] for c in cands},
+                    "mean_loss_sweep_all": {str(c): size_loss(rows, c)[0] for c in cands}}
     print(json.dumps({
-        "suite": "fit", "cells": len(rows),
+        "suite": "fit", "cells": len(rows), "size_guard": size_fit,
         "thresholds": dict(zip(("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min"), best)),
         "mean_loss_fit_seed0": loss(fit, best)[0], "mean_loss_heldout_seed1": loss(test, best)[0],
         "mean_loss_all": loss(rows, best)[0], "max_loss_all": loss(rows, best)[1],
@@ -386,7 +436,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "kernel", "fit"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "kernel", "fit"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -407,7 +457,8 @@ def main():
         return 2
     from paper_2106_16064_amd import binding as dg
     dg.lib()
-    return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "kernel": run_kernel}[args.suite](args)
+    return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
+            "kernel": run_kernel}[args.suite](args)
 
 
 if __name__ == "__main__":

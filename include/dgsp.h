@@ -74,10 +74,13 @@ typedef struct {
 /* Selector thresholds (Section 2.2 says they are set empirically and prints no
  * values; the defaults were fitted on MI355X).
  *   N <= n_parallel_max          -> parallel reduction, else sequential
- *   parallel:  avg_row >= pr_avg_row_min AND cv_row <= pr_cv_max -> row-split,
- *              else nnz-balanced (the cv guard is an addition: the paper's
- *              parallel-side rule looks at avg_row only; set pr_cv_max to a
- *              huge value to get the paper's rule verbatim)
+ *   parallel:  avg_row >= pr_avg_row_min AND cv_row <= pr_cv_max AND
+ *              nnz < pr_nnz_max -> row-split, else nnz-balanced (the last two
+ *              conditions are additions: the paper's parallel-side rule looks at
+ *              avg_row only.  The balanced kernel streams about a fifth faster
+ *              but needs a second, small launch, which pays off from roughly
+ *              2e7 stored entries on.  Set pr_cv_max to a huge value and
+ *              pr_nnz_max to INT64_MAX to get the paper's rule verbatim)
  *   sequential: cv_row > sr_cv_min AND stdv_row > sr_stdv_min -> nnz-balanced,
  *              else row-split (the paper's metric is cv_row alone; the second
  *              condition is an addition: with short rows even a large cv_row
@@ -89,6 +92,7 @@ typedef struct {
     double pr_cv_max;
     double sr_cv_min;
     double sr_stdv_min;
+    int64_t pr_nnz_max;
 } dgsp_thresholds_t;
 
 /*

@@ -231,14 +231,15 @@ int launch_nb_sr(const Problem& p) {
 }
 
 // ---------------------------------------------------------------- selector state
-// Defaults fitted on MI355X on the 24-matrix synthetic sweep (the paper prints
-// no threshold values, Section 2.2).
+// Defaults fitted on MI355X on the 24-matrix synthetic sweep, pr_nnz_max on larger
+// banded and random matrices (the paper prints no threshold values, Section 2.2).
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
     /* pr_avg_row_min  */ 0.0,
     /* pr_cv_max       */ 1.0,
     /* sr_cv_min       */ 0.3,
     /* sr_stdv_min     */ 3.0,
+    /* pr_nnz_max      */ 20000000,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
@@ -306,7 +307,7 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     const dgsp_thresholds_t& t = g_thresholds;
     if (N <= t.n_parallel_max) {
         // parallel reduction: long rows keep a row's lanes busy, short rows idle them
-        const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max;
+        const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max && f->nnz < t.pr_nnz_max;
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;
     }
     // sequential reduction: balance only when stdv_row / avg_row says rows are uneven

@@ -72,7 +72,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0)      # the paper's rule verbatim (no added guards)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62)      # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -95,7 +95,11 @@ def test_selection_rules_follow_the_decision_tree():
         t.n_parallel_max = 8
         dg.dgsp_set_thresholds(t)
         assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_PR
-        assert dg.dgsp_select_algo(None, 4) if False else True
+        t.pr_nnz_max = 50_000                                              # the added size guard
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(feat(64, 0.1, M=1000), 1) == dg.NB_PR   # 64 000 entries: second launch pays
+        assert dg.dgsp_select_algo(feat(64, 0.1, M=500), 1) == dg.RS_PR    # 32 000 entries
+        assert dg.dgsp_select_algo(feat(64, 0.1, M=1000), 64) == dg.RS_SR  # sequential side unaffected
         L = dg.lib()
         assert L.dgsp_select_algo(None, 4) == dg.AUTO
         assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
