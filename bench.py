@@ -18,6 +18,7 @@ prints one JSON line and writes details under gpurun_out/):
     --suite sweep     the 24-matrix x 10-N selector sweep (loss vs best kernel)
     --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
     --suite size      all four kernels on banded and random matrices of growing size, N <= 8
+    --suite ablation  each optimisation against the kernel without it, on 27 R-MAT matrices
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
 """
 from __future__ import annotations
@@ -27,6 +28,8 @@ import json
 import os
 import sys
 import time
+
+import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -101,6 +104,14 @@ class Rotation:
         j = 0 if warm else i % self.copies
         self.mats[j].spmm(self.X[j], algo=algo, Y=self.Y[j])
 
+    def ablation(self, i, algo, switches):
+        """The call with optimisations switched off (measurement aid)."""
+        from paper_2106_16064_amd import binding as dg
+        j = i % self.copies
+        m = self.mats[j]
+        dg.dgsp_spmm_csr_ablation(m.M, m.K, self.N, m.nnz, m.rowptr, m.colidx, m.vals, self.X[j], self.Y[j],
+                                  algo, switches, m.features)
+
     def phase(self, i, algo, phase):
         """One launch of a call (measurement aid): the prepare step or the main kernel alone."""
         from paper_2106_16064_amd import binding as dg
@@ -141,6 +152,26 @@ def time_events(fn_before, fn_timed, steps, warmup):
         evs[i][1].record()
     torch.cuda.synchronize()
     return [a.elapsed_time(b) for a, b in evs]
+
+
+def time_event_batches(fn_before, fn_timed, batch, batches, warmup):
+    """Mean duration (ms) of one fn_timed launch: each HIP-event pair brackets `batch` back-to-back
+    launches (i = 0..batch-1), so the pair's own cost is spread over the batch; fn_before(i) runs
+    untimed for every i before the batch starts."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(batches)]
+    for b in range(warmup + batches):
+        if fn_before:
+            for i in range(batch):
+                fn_before(i)
+        if b >= warmup:
+            evs[b - warmup][0].record()
+        for i in range(batch):
+            fn_timed(i)
+        if b >= warmup:
+            evs[b - warmup][1].record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(c) / batch for a, c in evs]
 
 
 def median(v):
@@ -215,8 +246,11 @@ def run_headline(args):
     ms_warm = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=True)
 
     # dominant kernel alone: the small prepare launch of the balanced kernels runs untimed first
-    ev = time_events(lambda i: rot.phase(i, chosen, dg.PHASE_PREPARE), lambda i: rot.phase(i, chosen, dg.PHASE_MAIN),
-                     args.steps, args.warmup)
+    # (once per buffer set), then one event pair brackets one main launch per buffer set
+    batches = max(1, args.steps // rot.copies)
+    ev = time_event_batches(lambda i: rot.phase(i, chosen, dg.PHASE_PREPARE),
+                            lambda i: rot.phase(i, chosen, dg.PHASE_MAIN), rot.copies, batches,
+                            max(1, args.warmup // rot.copies))
     ev_ms = sum(ev) / len(ev)
     kernel_name = {0: "rs_sr_kernel", 1: "rs_pr_kernel", 2: "nb_sr_kernel", 3: "nb_pr_kernel"}[chosen]
     floor_ms = gather_floor(rot) if N == 1 else None
@@ -252,7 +286,8 @@ def run_headline(args):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(f"{sel_name}/{args.workload or 'rmat_spmv'}/N{N}"),
-                     "kernel": f"dgsp::{kernel_name} (main launch alone, HIP events, mean of {len(ev)} launches)",
+                     "kernel": f"dgsp::{kernel_name} (main launch alone; HIP events around {len(ev)} batches of "
+                               f"{rot.copies} back-to-back launches, one per buffer set)",
                      "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms,
                      "gather_probe_ms": floor_ms},
         "cpu_baseline": cpu_baseline(A, X),
@@ -353,6 +388,66 @@ def run_size(args):
     return 0
 
 
+def run_ablation(args):
+    """Each optimisation of Section 2.1 against the kernel without it, on a grid of 27 R-MAT matrices
+    (3 sizes x 3 densities x 3 skews; the paper's own 27 parameter sets are not published):
+    N = 1: all four kernels (which wins how often; Section 2.1.1); N = 2: vector-type dense-row loads
+    against scalar loads = two passes (Section 2.1.2); N = 128: LDS-staged sparse rows against none
+    (Section 2.1.3)."""
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs("gpurun_out", exist_ok=True)
+    path = os.path.join("gpurun_out", args.out or "bench_ablation.jsonl")
+    skews = {"powerlaw": (0.57, 0.19, 0.19, 0.05), "mild": (0.45, 0.15, 0.15, 0.25), "uniform": (0.25, 0.25, 0.25, 0.25)}
+    k = max(5, min(args.steps, 20))
+
+    def med(fn):
+        return median(time_events(None, fn, k, 3))
+
+    rows = []
+    with open(path, "w") as fh:
+        for scale in (16, 18, 20):
+            for deg in (4, 16, 32):
+                for sname, abcd in skews.items():
+                    A = wl.rmat_csr(scale, deg, abcd, seed=0, values="uniform01")
+                    row = {"matrix": f"rmat_s{scale}_d{deg}_{sname}", "nnz": A.nnz, "stats": A.stats()}
+                    rot = Rotation(A, wl.dense_matrix(A.K, 1, "uniform", seed=0))
+                    row["spmv_ms"] = variant_table(rot, k, 3)
+                    del rot
+                    rot = Rotation(A, wl.dense_matrix(A.K, 2, "uniform", seed=0))
+                    row["n2_ms"] = {}
+                    for algo in (dg.RS_PR, dg.NB_PR):
+                        nm = dg.dgsp_algo_name(algo)
+                        row["n2_ms"][nm] = med(lambda i: rot.ablation(i, algo, 0))
+                        row["n2_ms"][nm + "_scalar_loads"] = med(lambda i: rot.ablation(i, algo, dg.ABL_SCALAR_DENSE_LOADS))
+                    del rot
+                    rot = Rotation(A, wl.dense_matrix(A.K, 128, "uniform", seed=0), copies=2)
+                    row["n128_ms"] = {
+                        "rs_sr": med(lambda i: rot.ablation(i, dg.RS_SR, 0)),
+                        "rs_sr_no_staging": med(lambda i: rot.ablation(i, dg.RS_SR, dg.ABL_NO_SPARSE_STAGING)),
+                        "nb_sr": med(lambda i: rot.ablation(i, dg.NB_SR, 0))}
+                    del rot
+                    rows.append(row)
+                    fh.write(json.dumps(row) + "\n")
+                    fh.flush()
+                    print(f"[ablation] {row['matrix']} done", file=sys.stderr, flush=True)
+
+    def geomean(v):
+        return float(np.exp(np.mean(np.log(v))))
+
+    wins = {}
+    for r in rows:
+        b = min(r["spmv_ms"], key=r["spmv_ms"].get)
+        wins[b] = wins.get(b, 0) + 1
+    print(json.dumps({
+        "suite": "ablation", "matrices": len(rows), "file": path,
+        "spmv_best_kernel_counts": wins,
+        "vector_dense_loads_speedup_N2": {a: geomean([r["n2_ms"][a + "_scalar_loads"] / r["n2_ms"][a] for r in rows])
+                                          for a in ("rs_pr", "nb_pr")},
+        "sparse_staging_speedup_N128": geomean([r["n128_ms"]["rs_sr_no_staging"] / r["n128_ms"]["rs_sr"] for r in rows])}))
+    return 0
+
+
 def run_fit(args):
     """Grid-fits the selector thresholds on the seed-0 matrices of a finished sweep
     (gpurun_out/bench_sweep.jsonl), checks them on the seed-1 matrices.  No GPU needed."""
@@ -436,7 +531,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "kernel", "fit"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "kernel", "fit"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -458,7 +553,7 @@ def main():
     from paper_2106_16064_amd import binding as dg
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
-            "kernel": run_kernel}[args.suite](args)
+            "ablation": run_ablation, "kernel": run_kernel}[args.suite](args)
 
 
 if __name__ == "__main__":

@@ -195,6 +195,32 @@ int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
                         const dgsp_features_t *features, void *stream);
 
 /*
+ * Measurement aid: the same multiplication with one of the paper's optimisations
+ * switched off, for the comparisons of Sections 2.1.2 and 2.1.3.  Same arguments,
+ * layouts, result and error behaviour as dgsp_spmm_csr_nnz; `switches` is a
+ * bit-wise OR of
+ *   DGSP_ABL_SCALAR_DENSE_LOADS  dense rows are read one float at a time, so a
+ *                                parallel-reduction SpMM becomes N passes over the
+ *                                sparse matrix, one per dense column: the
+ *                                "N times SpMV" that vector-type dense-row loading
+ *                                is measured against (Section 2.1.2).  Any algo.
+ *   DGSP_ABL_NO_SPARSE_STAGING   sequential reduction without the LDS tile: every
+ *                                lane reads colidx/vals from memory itself, the
+ *                                "pure sequential reduction" that coalesced
+ *                                sparse-row caching is measured against
+ *                                (Section 2.1.3).  Only DGSP_RS_SR, else
+ *                                DGSP_ERR_UNSUPPORTED.
+ * Unknown bits -> DGSP_ERR_INVALID_ARG.  algo must be one of the four kernels.
+ * `features` may be NULL (host pointer otherwise; nnz and col_span are used).
+ */
+#define DGSP_ABL_SCALAR_DENSE_LOADS 1
+#define DGSP_ABL_NO_SPARSE_STAGING 2
+int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                           const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                           const float *X, float *Y, int algo, int switches,
+                           const dgsp_features_t *features, void *stream);
+
+/*
  * Measurement aid, not part of the method: out[t] = sum of x[idx[i]] over the
  * i that thread t visits (device buffers; idx int32[n] with 0 <= idx[i] < the
  * length of x; out fp32[dgsp_gather_probe_out_len()]).  It does nothing but

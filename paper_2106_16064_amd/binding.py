@@ -22,8 +22,10 @@ EXPORTS = (
     "dgsp_get_thresholds", "dgsp_set_thresholds", "dgsp_features_from_rowptr_host",
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
+    "dgsp_spmm_csr_ablation",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
+ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING = 1, 2
 
 
 class Features(ctypes.Structure):
@@ -79,6 +81,8 @@ def lib():
         L.dgsp_features_from_csr_host.argtypes = [i64, i64, vp, vp, ctypes.POINTER(Features)]
         L.dgsp_spmm_csr_phase.restype = ci
         L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
+        L.dgsp_spmm_csr_ablation.restype = ci
+        L.dgsp_spmm_csr_ablation.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
         L.dgsp_gather_probe.restype = ci
         L.dgsp_gather_probe.argtypes = [vp, vp, vp, i64, vp]
         L.dgsp_gather_probe_out_len.restype = i64
@@ -146,6 +150,16 @@ def dgsp_spmm_csr_phase(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, phase, f
                                    int(algo), int(phase), ctypes.byref(features) if features is not None else None,
                                    _stream(stream))
     _check(rc, "dgsp_spmm_csr_phase")
+
+
+def dgsp_spmm_csr_ablation(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, switches, features=None, stream=None):
+    """The multiplication with optimisations switched off (measurement aid): ABL_SCALAR_DENSE_LOADS,
+    ABL_NO_SPARSE_STAGING."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    rc = lib().dgsp_spmm_csr_ablation(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
+                                      int(algo), int(switches),
+                                      ctypes.byref(features) if features is not None else None, _stream(stream))
+    _check(rc, "dgsp_spmm_csr_ablation")
 
 
 def dgsp_gather_probe(out, x, idx, n=None, stream=None):

@@ -45,7 +45,7 @@ inline int ilog2_ceil(long long v) {   // smallest l with 2^l >= v  (v >= 1)
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // widest vector width that N and the buffers allow (Section 2.1.2: float2 / float4)
-inline int vector_width(long long N, const float* X, const float* Y) {
+inline int widest_vector(long long N, const float* X, const float* Y) {
     if (N % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) return 4;
     if (N % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) return 2;
     return 1;
@@ -68,7 +68,12 @@ struct Problem {
     hipStream_t stream;
     int phase = DGSP_PHASE_ALL;
     double col_span = 0.0;   // mean column span of a row / K; 0 = unknown
+    int switches = 0;        // DGSP_ABL_* (measurement aids)
 };
+
+inline int vector_width(const Problem& p) {
+    return (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) ? 1 : widest_vector(p.N, p.X, p.Y);
+}
 
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
     do {                                                                                      \
@@ -117,7 +122,7 @@ int launch_rs_pr_v(const Problem& p) {
 
 int launch_rs_pr(const Problem& p) {
     const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p.N, p.X, p.Y)) {
+    switch (vector_width(p)) {
         case 4: return xb ? launch_rs_pr_v<4, true>(p) : launch_rs_pr_v<4, false>(p);
         case 2: return xb ? launch_rs_pr_v<2, true>(p) : launch_rs_pr_v<2, false>(p);
         default: return xb ? launch_rs_pr_v<1, true>(p) : launch_rs_pr_v<1, false>(p);
@@ -150,9 +155,30 @@ int launch_rs_sr_v(const Problem& p) {
     return DGSP_OK;
 }
 
+template <int V>
+int launch_rs_sr_direct_v(const Problem& p) {
+    const int logG = sr_lanes_log2(p.N, V);
+    const long long cols_per_block = (long long)V << logG;
+    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
+    const int rows_per_wave = kWave >> logG;
+    const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
+    const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
+    const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
+    DGSP_LAUNCH((rs_sr_direct_kernel<V>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    return DGSP_OK;
+}
+
 int launch_rs_sr(const Problem& p) {
+    if (p.switches & DGSP_ABL_NO_SPARSE_STAGING) {
+        switch (vector_width(p)) {
+            case 4: return launch_rs_sr_direct_v<4>(p);
+            case 2: return launch_rs_sr_direct_v<2>(p);
+            default: return launch_rs_sr_direct_v<1>(p);
+        }
+    }
     const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p.N, p.X, p.Y)) {
+    switch (vector_width(p)) {
         case 4:
             if (banded(p)) return xb ? launch_rs_sr_v<4, true, 4>(p) : launch_rs_sr_v<4, false, 4>(p);
             return xb ? launch_rs_sr_v<4, true, 1>(p) : launch_rs_sr_v<4, false, 1>(p);
@@ -195,7 +221,7 @@ int launch_nb_pr_v(const Problem& p) {
 }
 
 int launch_nb_pr(const Problem& p) {
-    switch (vector_width(p.N, p.X, p.Y)) {
+    switch (vector_width(p)) {
         case 4: return launch_nb_pr_v<4, 1>(p);
         case 2: return launch_nb_pr_v<2, 2>(p);
         default: return launch_nb_pr_v<1, 2>(p);
@@ -219,7 +245,7 @@ int launch_nb_sr_v(const Problem& p) {
 
 int launch_nb_sr(const Problem& p) {
     const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p.N, p.X, p.Y)) {
+    switch (vector_width(p)) {
         case 4:
             if (banded(p)) return xb ? launch_nb_sr_v<4, true, 4>(p) : launch_nb_sr_v<4, false, 4>(p);
             return xb ? launch_nb_sr_v<4, true, 1>(p) : launch_nb_sr_v<4, false, 1>(p);
@@ -244,7 +270,7 @@ dgsp_thresholds_t g_thresholds = {
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
         const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
-        double col_span = 0.0) {
+        double col_span = 0.0, int switches = 0) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
     if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return DGSP_OK;
@@ -256,7 +282,7 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
 
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
-    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span};
+    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span, switches};
     switch (algo) {
         case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
         case DGSP_RS_PR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_pr(p);
@@ -288,6 +314,17 @@ extern "C" int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase,
                features ? features->col_span : 0.0);
+}
+
+extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                      const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
+                                      int switches, const dgsp_features_t* features, void* stream) {
+    if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
+    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING)) return DGSP_ERR_INVALID_ARG;
+    if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
+    if (features && nnz < 0) nnz = features->nnz;
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
+               features ? features->col_span : 0.0, switches);
 }
 
 extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_features_t* features,

@@ -154,10 +154,12 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
 
 constexpr int kRsSrTile = 512;   // cached pairs per wave and round
 // DEPTH (template parameter of the sequential kernels) = dense-row loads a lane keeps in flight.
-// More is not better: a wave's load of 64 x 16 bytes is 1 KB, and once the loads in flight on a
-// CU exceed what its L1 can hold the misses stall each other (measured: rows of random columns,
-// N = 32, 182 us at depth 1, 266 us at depth 4); rows that hit in cache want the latency hidden
-// instead (27-point stencil, N = 8: 204 us at depth 4, 260 us at depth 1).  The host picks.
+// More is not always better.  With ascending columns the lanes of a wave, and the waves that
+// start together, sweep X from low to high rows in step; every load in flight widens the window
+// of X they touch at one time, and once that window outgrows the L2 the hit rate drops (measured
+// on 2^20 rows of 27 uniform columns, N = 4: 58 % L2 hits and 224 us at depth 1, 26 % and 373 us
+// at depth 4).  Rows that hit in cache anyway want the latency hidden instead (27-point stencil,
+// N = 8: 204 us at depth 4, 260 us at depth 1), and so do rows of uneven length.  The host picks.
 
 template <int V, bool XBUF, int DEPTH>
 __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
@@ -244,6 +246,45 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
             }
         }
         if (live && col_ok) store_vec<V>(Y + (size_t)row * N + n, acc);
+    }
+}
+
+// Row-split sequential reduction WITHOUT the LDS tile (the kernel Section 2.1.3 compares its
+// sparse-row caching against): same row and column mapping as rs_sr_kernel, but every lane of a
+// group reads colidx[p] and vals[p] itself, straight from memory, one entry after the other.
+// Kept for measurements only.
+template <int V>
+__global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, const int* __restrict__ rowptr,
+                                                               const int* __restrict__ colidx,
+                                                               const float* __restrict__ vals,
+                                                               const float* __restrict__ X, float* __restrict__ Y,
+                                                               int logG) {
+    const int lane = lane_id();
+    const int G = 1 << logG;
+    const int gl = lane & (G - 1);
+    const int g = lane >> logG;
+    const int rows_per_wave = kWave >> logG;
+    const long long n = ((long long)blockIdx.y * G + gl) * V;
+    const bool col_ok = n < N;
+    const unsigned nwaves = gridDim.x * kWavesPerBlock;
+    const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
+    const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;
+    for (unsigned rg = gw; rg < ngroups; rg += nwaves) {
+        const long long row = (long long)rg * rows_per_wave + g;
+        if (row >= M || !col_ok) continue;
+        const int rs = rowptr[row], re = rowptr[row + 1];
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+        for (int p = rs; p < re; ++p) {
+            const int c = colidx[p];
+            const float a = vals[p];
+            float x[V];
+            load_vec<V>(X + (size_t)c * N + n, x);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(a, x[i], acc[i]);
+        }
+        store_vec<V>(Y + (size_t)row * N + n, acc);
     }
 }
 

@@ -318,3 +318,46 @@ def test_column_span_hint_changes_nothing_but_speed(dg, N):
         torch.cuda.synchronize()
         ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
         assert ok, (ALGO_NAMES[algo], N, worst)
+
+
+# ------------------------------------------------------------------ optimisations switched off (Sections 2.1.2, 2.1.3)
+def _ablation_run(dg, A, X, algo, switches):
+    import torch
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).to("cuda:0")
+    dY = torch.full((A.M, X.shape[1]), float("nan"), dtype=torch.float32, device="cuda:0")
+    dg.dgsp_spmm_csr_ablation(A.M, A.K, X.shape[1], A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, algo, switches,
+                              dA.features)
+    torch.cuda.synchronize()
+    return dY.cpu().numpy()
+
+
+@pytest.mark.parametrize("N", [1, 2, 4, 7, 8, 64, 130])
+def test_switched_off_optimisations_compute_the_same_product(dg, N):
+    """Scalar dense-row loads (all four kernels) and the sequential kernel without its LDS tile
+    change the schedule only: same acceptance bound against the oracle."""
+    A = wl.sweep_csr(3000, 16, "lognormal", seed=N)
+    X = wl.dense_matrix(A.K, N, "normal", seed=N)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    cases = [(a, dg.ABL_SCALAR_DENSE_LOADS) for a in (0, 1, 2, 3)]
+    cases += [(0, dg.ABL_NO_SPARSE_STAGING), (0, dg.ABL_NO_SPARSE_STAGING | dg.ABL_SCALAR_DENSE_LOADS), (3, 0)]
+    for algo, sw in cases:
+        print(f"[case] ablation N={N} algo={ALGO_NAMES[algo]} switches={sw}", flush=True)
+        Y = _ablation_run(dg, A, X, algo, sw)
+        assert not np.isnan(Y).any()
+        ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+        assert ok, f"{ALGO_NAMES[algo]} switches={sw} N={N}: worst |err|/bound = {worst:.3e}"
+
+
+def test_ablation_entry_rejects_what_it_does_not_offer(dg):
+    import torch
+    A = wl.poisson_csr(64, 64, 4.0, seed=0)
+    dA = dg.DeviceCsr(A)
+    X = torch.zeros((A.K, 2), device="cuda:0")
+    Y = torch.zeros((A.M, 2), device="cuda:0")
+    L = dg.lib()
+    args = (A.M, A.K, 2, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_NO_SPARSE_STAGING, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 8, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ablation(*args, dg.AUTO, 0, None, None) == dg.ERR_INVALID_ARG
+    torch.cuda.synchronize()
