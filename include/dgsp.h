@@ -175,6 +175,40 @@ int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t *rowptr_host
                                 const int32_t *colidx_host, dgsp_features_t *out);
 
 /*
+ * The same statistics from a matrix that lives in DEVICE memory: one pass over
+ * rowptr (and, if colidx is not NULL, over every row's columns for col_span; a
+ * NULL colidx leaves col_span 0).  All sums are integer sums, so the result equals
+ * dgsp_features_from_csr_host on a host copy bit for bit.
+ *   rowptr, colidx  device, as in dgsp_spmm_csr
+ *   workspace       device, DGSP_FEATURES_WORKSPACE_BYTES bytes, 8-byte aligned,
+ *                   caller-owned, overwritten; needs no initialisation
+ *   out             host
+ * The call enqueues two small launches and a copy on `stream` and WAITS for them
+ * (the result goes to host memory).  Errors as the host versions; a NULL or
+ * misaligned workspace with M > 0 -> DGSP_ERR_INVALID_ARG.
+ */
+#define DGSP_FEATURES_WORKSPACE_BYTES 64
+int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t *rowptr, const int32_t *colidx,
+                                  void *workspace, dgsp_features_t *out, void *stream);
+
+/*
+ * Profile-based selection (Section 3 describes running all kernels once off-line
+ * and keeping the fastest as the alternative to the rules): runs each of the four
+ * kernels on the given buffers - one untimed call, then `reps` (clamped to
+ * 1..100) calls bracketed by events on `stream` - and reports the fastest.
+ *   ms    host, 4 floats or NULL: best time of each kernel in milliseconds,
+ *         indexed by dgsp_algo_t (INFINITY for a kernel that rejects the shape)
+ *   best  host, receives the dgsp_algo_t with the smallest time
+ * Other arguments as dgsp_spmm_csr_phase.  Y is overwritten with the product
+ * (every kernel computes the same one).  The call WAITS for its launches; it
+ * allocates no device memory.  Errors of the kernels are passed on.
+ */
+int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                  const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                  const float *X, float *Y, const dgsp_features_t *features,
+                  int reps, float *ms, int *best, void *stream);
+
+/*
  * Measurement aid: the same multiplication, one step at a time.  The two
  * nnz-balanced kernels are two launches per call - a small "prepare" launch
  * (zeroes the rows that are later combined with atomic adds) and the main

@@ -22,10 +22,11 @@ EXPORTS = (
     "dgsp_get_thresholds", "dgsp_set_thresholds", "dgsp_features_from_rowptr_host",
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
-    "dgsp_spmm_csr_ablation",
+    "dgsp_spmm_csr_ablation", "dgsp_features_from_csr_device", "dgsp_autotune",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING = 1, 2
+FEATURES_WORKSPACE_BYTES = 64
 
 
 class Features(ctypes.Structure):
@@ -81,6 +82,11 @@ def lib():
         L.dgsp_features_from_csr_host.argtypes = [i64, i64, vp, vp, ctypes.POINTER(Features)]
         L.dgsp_spmm_csr_phase.restype = ci
         L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
+        L.dgsp_features_from_csr_device.restype = ci
+        L.dgsp_features_from_csr_device.argtypes = [i64, i64, vp, vp, vp, ctypes.POINTER(Features), vp]
+        L.dgsp_autotune.restype = ci
+        L.dgsp_autotune.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.POINTER(Features), ci,
+                                    ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci), vp]
         L.dgsp_spmm_csr_ablation.restype = ci
         L.dgsp_spmm_csr_ablation.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
         L.dgsp_gather_probe.restype = ci
@@ -160,6 +166,30 @@ def dgsp_spmm_csr_ablation(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, switc
                                       int(algo), int(switches),
                                       ctypes.byref(features) if features is not None else None, _stream(stream))
     _check(rc, "dgsp_spmm_csr_ablation")
+
+
+def dgsp_features_from_csr_device(M, K, rowptr, colidx=None, workspace=None, stream=None) -> Features:
+    """Row statistics of a matrix in device memory (waits for the result)."""
+    import torch
+    if workspace is None:
+        workspace = torch.empty(FEATURES_WORKSPACE_BYTES // 8, dtype=torch.int64, device=rowptr.device)
+    f = Features()
+    rc = lib().dgsp_features_from_csr_device(M, K, _ptr(rowptr), _ptr(colidx) if colidx is not None else None,
+                                             _ptr(workspace), ctypes.byref(f), _stream(stream))
+    _check(rc, "dgsp_features_from_csr_device")
+    return f
+
+
+def dgsp_autotune(M, K, N, nnz, rowptr, colidx, vals, X, Y, features=None, reps=5, stream=None):
+    """Times the four kernels on these buffers; returns (fastest algo, [ms of each kernel])."""
+    _check_device_tensors(M, K, N, rowptr, colidx, vals, X, Y)
+    ms = (ctypes.c_float * 4)()
+    best = ctypes.c_int(-1)
+    rc = lib().dgsp_autotune(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
+                             ctypes.byref(features) if features is not None else None, int(reps), ms,
+                             ctypes.byref(best), _stream(stream))
+    _check(rc, "dgsp_autotune")
+    return best.value, list(ms)
 
 
 def dgsp_gather_probe(out, x, idx, n=None, stream=None):
@@ -248,6 +278,19 @@ class DeviceCsr:
         self.colidx = torch.from_numpy(A.colidx).to(device)
         self.vals = torch.from_numpy(A.vals).to(device)
         self.features = dgsp_features_from_csr_host(A.M, A.K, A.rowptr, A.colidx)
+        self.tuned = {}        # N -> kernel found fastest by autotune()
+
+    def autotune(self, X, reps=5, Y=None):
+        """Times the four kernels for this matrix and this width of X and remembers the winner:
+        later ``spmm(X, algo=AUTO)`` calls with the same width use it instead of the rules."""
+        import torch
+        N = X.shape[1] if X.dim() == 2 else 1
+        if Y is None:
+            Y = torch.empty((self.M, N), dtype=torch.float32, device=X.device)
+        best, ms = dgsp_autotune(self.M, self.K, N, self.nnz, self.rowptr, self.colidx, self.vals, X, Y,
+                                 self.features, reps)
+        self.tuned[N] = best
+        return best, ms
 
     def spmm(self, X, algo=AUTO, Y=None, use_nnz=True, stream=None):
         """Y = A X.  ``algo=AUTO`` applies the selection rules to this matrix's features."""
@@ -255,6 +298,8 @@ class DeviceCsr:
         N = X.shape[1] if X.dim() == 2 else 1
         if Y is None:
             Y = torch.empty((self.M, N), dtype=torch.float32, device=X.device)
+        if algo == AUTO and N in getattr(self, "tuned", {}):
+            algo = self.tuned[N]
         if algo == AUTO:
             dgsp_spmm_csr_auto(self.M, self.K, N, self.features, self.rowptr, self.colidx, self.vals, X, Y, stream)
         elif use_nnz:

@@ -406,8 +406,9 @@ extern "C" int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t* 
     if (rc != DGSP_OK) return rc;
     if (out->nnz > 0 && !colidx) return DGSP_ERR_INVALID_ARG;
     if (M == 0 || K == 0 || out->nnz == 0) return DGSP_OK;
-    // mean over the non-empty rows of (largest - smallest column + 1) / K
-    double sum = 0.0;
+    // mean over the non-empty rows of (largest - smallest column + 1) / K; the spans are summed as
+    // integers so that the device version, which adds them in any order, gives the same bits
+    uint64_t sum = 0;
     int64_t rows = 0;
     for (int64_t i = 0; i < M; ++i) {
         const int64_t s = rowptr[i], e = rowptr[i + 1];
@@ -422,10 +423,88 @@ extern "C" int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t* 
             if (sorted) hi = colidx[e - 1];
             else for (int64_t p = s; p < e; ++p) { lo = colidx[p] < lo ? colidx[p] : lo; hi = colidx[p] > hi ? colidx[p] : hi; }
         }
-        sum += (double)(hi - lo + 1) / (double)K;
+        sum += (uint64_t)((int64_t)hi - (int64_t)lo + 1);
         ++rows;
     }
-    out->col_span = rows ? sum / (double)rows : 0.0;
+    out->col_span = rows ? (double)sum / ((double)K * (double)rows) : 0.0;
+    return DGSP_OK;
+}
+
+extern "C" int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,
+                                             void* workspace, dgsp_features_t* out, void* stream) {
+    if (M < 0 || K < 0 || !out || (!rowptr && M > 0)) return DGSP_ERR_INVALID_ARG;
+    if (M > (int64_t)INT32_MAX - 4096) return DGSP_ERR_INVALID_ARG;
+    dgsp_features_t f{};
+    f.M = M; f.K = K;
+    if (M == 0) { *out = f; return DGSP_OK; }
+    if (!workspace || !aligned(workspace, 8)) return DGSP_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned long long* ws = static_cast<unsigned long long*>(workspace);
+    hipLaunchKernelGGL(features_init_kernel, dim3(1), dim3(kWave), 0, st, ws);
+    const long long waves = (M + kWave - 1) / kWave;
+    const dim3 grid(clamp_blocks((waves + kWavesPerBlock - 1) / kWavesPerBlock, (long long)device_info().cus * kBlocksPerCu));
+    hipLaunchKernelGGL(features_kernel, grid, dim3(kBlock), 0, st, (int)M, rowptr, K > 0 ? colidx : nullptr, ws);
+    if (hipGetLastError() != hipSuccess) return DGSP_ERR_LAUNCH;
+    unsigned long long h[kFeatureWords];
+    if (hipMemcpyAsync(h, ws, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return DGSP_ERR_LAUNCH;
+    if (hipStreamSynchronize(st) != hipSuccess) return DGSP_ERR_LAUNCH;
+    if (h[5] != 0 || h[6] != 0) return DGSP_ERR_INVALID_ARG;       // decreasing row pointers, rowptr[0] != 0
+    f.nnz = (int64_t)h[7];
+    f.max_row = (int64_t)h[1]; f.min_row = (int64_t)h[2];
+    f.avg_row = (double)f.nnz / (double)M;
+    const unsigned __int128 num = (unsigned __int128)h[0] * (unsigned __int128)M
+                                  - (unsigned __int128)((uint64_t)f.nnz) * (uint64_t)f.nnz;
+    f.stdv_row = std::sqrt((double)num / ((double)M * (double)M));
+    f.cv_row = f.avg_row > 0 ? f.stdv_row / f.avg_row : 0.0;
+    f.col_span = (colidx && K > 0 && h[3] > 0) ? (double)h[4] / ((double)K * (double)h[3]) : 0.0;
+    *out = f;
+    return DGSP_OK;
+}
+
+extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                             const int32_t* colidx, const float* vals, const float* X, float* Y,
+                             const dgsp_features_t* features, int reps, float* ms, int* best, void* stream) {
+    if (!best) return DGSP_ERR_INVALID_ARG;
+    if (reps < 1) reps = 1;
+    if (reps > 100) reps = 100;
+    if (features && nnz < 0) nnz = features->nnz;
+    const double col_span = features ? features->col_span : 0.0;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return DGSP_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return DGSP_ERR_LAUNCH; }
+    float t[4];
+    int rc = DGSP_OK;
+    float best_ms = INFINITY;
+    int best_algo = -1;
+    for (int algo = DGSP_RS_SR; algo <= DGSP_NB_PR && rc == DGSP_OK; ++algo) {
+        t[algo] = INFINITY;
+        // one untimed call first (first-use costs, caches), then `reps` timed ones; keep the fastest
+        for (int r = 0; r <= reps; ++r) {
+            if (r > 0 && hipEventRecord(e0, st) != hipSuccess) { rc = DGSP_ERR_LAUNCH; break; }
+            const int one = run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
+                                col_span);
+            if (one == DGSP_ERR_UNSUPPORTED) break;            // this kernel does not take the shape: skip it
+            if (one != DGSP_OK) { rc = one; break; }
+            if (r == 0) continue;
+            float dt = 0.0f;
+            if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&dt, e0, e1) != hipSuccess) { rc = DGSP_ERR_LAUNCH; break; }
+            t[algo] = dt < t[algo] ? dt : t[algo];
+            if (dt > 20.0f * best_ms) break;                   // hopeless: do not repeat a kernel 20x off the pace
+        }
+        if (t[algo] < best_ms) { best_ms = t[algo]; best_algo = algo; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != DGSP_OK) return rc;
+    if (hipStreamSynchronize(st) != hipSuccess) return DGSP_ERR_LAUNCH;
+    if (ms) for (int a = 0; a < 4; ++a) ms[a] = t[a];
+    if (best_algo < 0) {
+        // nothing was timed (M == 0 or N == 0: every call returns at once): any kernel will do
+        best_algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
+    }
+    *best = best_algo;
     return DGSP_OK;
 }
 

@@ -880,6 +880,105 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 }
 
 // ===========================================================================
+// row statistics of a matrix that lives in device memory (the selector's metrics, Section 2.2)
+// ===========================================================================
+// ws[0] sum of len^2, [1] max len, [2] min len, [3] non-empty rows whose span was taken,
+// [4] sum of (largest - smallest column + 1), [5] a row pointer decreased, [6] rowptr[0], [7] rowptr[M].
+// All integer, so the result does not depend on the order in which waves arrive.
+constexpr int kFeatureWords = 8;
+constexpr int kFeatureLongRow = 128;   // longer rows are scanned by the whole wave
+
+__global__ void features_init_kernel(unsigned long long* __restrict__ ws) {
+    if (blockIdx.x == 0 && threadIdx.x < kFeatureWords) ws[threadIdx.x] = threadIdx.x == 2 ? ~0ull : 0ull;
+}
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
+    const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, mask, kWave);
+    const unsigned hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), mask, kWave);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+__global__ __launch_bounds__(kBlock) void features_kernel(int M, const int* __restrict__ rowptr,
+                                                           const int* __restrict__ colidx,
+                                                           unsigned long long* __restrict__ ws) {
+    const int lane = lane_id();
+    const long long nwaves = (long long)gridDim.x * kWavesPerBlock;
+    const long long gw = (long long)blockIdx.x * kWavesPerBlock + wave_in_block();
+    unsigned long long sq = 0, mx = 0, mn = ~0ull, rows = 0, span = 0, bad = 0;
+    for (long long r0 = gw * kWave; r0 < M; r0 += nwaves * kWave) {
+        const long long row = r0 + lane;
+        const bool live = row < M;
+        int s = 0, e = 0;
+        if (live) { s = rowptr[row]; e = rowptr[row + 1]; }
+        long long len = (long long)e - (long long)s;
+        if (len < 0) { bad = 1; len = 0; }
+        if (live) {
+            const unsigned long long l = (unsigned long long)len;
+            sq += l * l;
+            mx = l > mx ? l : mx;
+            mn = l < mn ? l : mn;
+        }
+        if (colidx != nullptr) {
+            const bool long_row = live && len > kFeatureLongRow;
+            if (live && len > 0 && !long_row) {
+                int lo = colidx[s], hi = lo;
+                for (int p = s + 1; p < e; ++p) {
+                    const int c = colidx[p];
+                    lo = c < lo ? c : lo;
+                    hi = c > hi ? c : hi;
+                }
+                span += (unsigned long long)((long long)hi - lo + 1);
+                rows += 1;
+            }
+            unsigned long long todo = __ballot(long_row);
+            while (todo) {                                   // wave-uniform
+                const int src = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                const int ss = __shfl(s, src, kWave), ee = __shfl(e, src, kWave);
+                int lo = 0x7fffffff, hi = -0x7fffffff - 1;
+                for (int p = ss + lane; p < ee; p += kWave) {
+                    const int c = colidx[p];
+                    lo = c < lo ? c : lo;
+                    hi = c > hi ? c : hi;
+                }
+#pragma unroll
+                for (int m = 1; m < kWave; m <<= 1) {
+                    const int ol = __shfl_xor(lo, m, kWave), oh = __shfl_xor(hi, m, kWave);
+                    lo = ol < lo ? ol : lo;
+                    hi = oh > hi ? oh : hi;
+                }
+                if (lane == src) {
+                    span += (unsigned long long)((long long)hi - lo + 1);
+                    rows += 1;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        sq += shfl_xor_u64(sq, m);
+        rows += shfl_xor_u64(rows, m);
+        span += shfl_xor_u64(span, m);
+        bad |= shfl_xor_u64(bad, m);
+        const unsigned long long omx = shfl_xor_u64(mx, m), omn = shfl_xor_u64(mn, m);
+        mx = omx > mx ? omx : mx;
+        mn = omn < mn ? omn : mn;
+    }
+    if (lane == 0) {
+        atomicAdd(&ws[0], sq);
+        atomicMax(&ws[1], mx);
+        atomicMin(&ws[2], mn);
+        if (rows) atomicAdd(&ws[3], rows);
+        if (span) atomicAdd(&ws[4], span);
+        if (bad) atomicMax(&ws[5], 1ull);
+        if (gw == 0) {
+            ws[6] = (unsigned long long)(long long)rowptr[0];
+            ws[7] = (unsigned long long)(long long)rowptr[M];
+        }
+    }
+}
+
+// ===========================================================================
 // measurement aids: pure gather, plain streaming copy
 // ===========================================================================
 

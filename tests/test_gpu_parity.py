@@ -361,3 +361,96 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 8, None, None) == dg.ERR_INVALID_ARG
     assert L.dgsp_spmm_csr_ablation(*args, dg.AUTO, 0, None, None) == dg.ERR_INVALID_ARG
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ row statistics on the device, profile-based selection
+@pytest.mark.parametrize("gen", ["poisson", "rmat", "stencil", "hub", "unsorted", "empty_rows"])
+def test_device_features_equal_the_host_ones(dg, gen):
+    """Section 2.2's metrics computed by the GPU from device CSR: integer sums, so bit-equal to the
+    host pass, which tests/test_host_api.py pins to closed forms and to the oracle's statistics."""
+    import torch
+    if gen == "poisson":
+        A = wl.poisson_csr(5000, 3000, 6.0, seed=1)
+    elif gen == "rmat":
+        A = wl.rmat_csr(scale=14, avg_degree=16, seed=3)
+    elif gen == "stencil":
+        A = wl.stencil27_csr(17, seed=0)
+    elif gen == "hub":
+        lens = np.full(3000, 2); lens[7] = 2900; lens[2999] = 700; lens[100:200] = 0
+        A = wl.csr_from_lens(lens, 3000, seed=5, name="hub")
+    elif gen == "unsorted":
+        A = wl.sweep_csr(2000, 16, "lognormal", seed=2)
+        rng = np.random.default_rng(0)
+        for i in range(A.M):           # shuffle the columns inside every row
+            s, e = A.rowptr[i], A.rowptr[i + 1]
+            A.colidx[s:e] = rng.permutation(A.colidx[s:e])
+    else:
+        lens = np.zeros(1000, dtype=np.int64); lens[::97] = 5
+        A = wl.csr_from_lens(lens, 1 << 20, seed=6, name="mostly_empty")
+    host = dg.dgsp_features_from_csr_host(A.M, A.K, A.rowptr, A.colidx)
+    rp = torch.from_numpy(A.rowptr).cuda()
+    ci = torch.from_numpy(A.colidx).cuda()
+    dev = dg.dgsp_features_from_csr_device(A.M, A.K, rp, ci)
+    for name in ("M", "K", "nnz", "max_row", "min_row", "avg_row", "stdv_row", "cv_row", "col_span"):
+        assert getattr(dev, name) == getattr(host, name), name
+    # and against the oracle's own statistics (numpy)
+    ref = oracle.row_features(A.rowptr)
+    assert (dev.nnz, dev.max_row, dev.min_row) == (ref["nnz"], ref["max_row"], ref["min_row"])
+    assert dev.avg_row == pytest.approx(ref["avg_row"], rel=1e-12)
+    assert dev.stdv_row == pytest.approx(ref["stdv_row"], rel=1e-9, abs=1e-12)
+    # col_span against its definition, written out with numpy on the host copy
+    lens = np.diff(A.rowptr)
+    spans = [int(A.colidx[s:e].max()) - int(A.colidx[s:e].min()) + 1
+             for s, e in zip(A.rowptr[:-1], A.rowptr[1:]) if e > s]
+    assert dev.col_span == pytest.approx(sum(spans) / (A.K * len(spans)) if spans else 0.0, rel=1e-12)
+    assert int((lens > 0).sum()) == len(spans)
+    # without colidx the row statistics are the same and col_span stays 0
+    dev2 = dg.dgsp_features_from_csr_device(A.M, A.K, rp, None)
+    assert dev2.col_span == 0.0 and dev2.stdv_row == host.stdv_row and dev2.nnz == host.nnz
+
+
+def test_device_features_reject_malformed_input(dg):
+    import torch
+    L = dg.lib()
+    f = dg.Features()
+    ws = torch.empty(8, dtype=torch.int64, device="cuda:0")
+    bad = torch.tensor([0, 3, 2, 5], dtype=torch.int32, device="cuda:0")        # decreases
+    assert L.dgsp_features_from_csr_device(3, 8, bad.data_ptr(), None, ws.data_ptr(), ctypes_byref(f), None) == dg.ERR_INVALID_ARG
+    off = torch.tensor([1, 3, 4, 5], dtype=torch.int32, device="cuda:0")        # does not start at 0
+    assert L.dgsp_features_from_csr_device(3, 8, off.data_ptr(), None, ws.data_ptr(), ctypes_byref(f), None) == dg.ERR_INVALID_ARG
+    ok = torch.tensor([0, 3, 4, 5], dtype=torch.int32, device="cuda:0")
+    assert L.dgsp_features_from_csr_device(3, 8, ok.data_ptr(), None, None, ctypes_byref(f), None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_features_from_csr_device(3, 8, ok.data_ptr(), None, ws.data_ptr() + 4, ctypes_byref(f), None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_features_from_csr_device(0, 8, None, None, None, ctypes_byref(f), None) == dg.OK and f.nnz == 0
+    assert L.dgsp_features_from_csr_device(3, 8, ok.data_ptr(), None, ws.data_ptr(), ctypes_byref(f), None) == dg.OK
+    assert (f.nnz, f.max_row, f.min_row) == (5, 3, 1)
+
+
+def ctypes_byref(x):
+    import ctypes
+    return ctypes.byref(x)
+
+
+@pytest.mark.parametrize("N", [1, 8])
+def test_autotune_reports_the_fastest_kernel_and_leaves_the_product(dg, N):
+    import torch
+    A = wl.rmat_csr(scale=15, avg_degree=16, seed=4)
+    X = wl.dense_matrix(A.K, N, "uniform", seed=4)
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    dY = torch.full((A.M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    best, ms = dg.dgsp_autotune(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, dA.features, reps=3)
+    assert best in (0, 1, 2, 3) and len(ms) == 4
+    assert all(np.isfinite(t) and t > 0 for t in ms)
+    assert ms[best] == min(ms)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+    assert ok, worst
+    # a skewed graph: the row-split sequential kernel cannot be the winner
+    assert best != dg.RS_SR
+    # the matrix object remembers the winner and uses it for AUTO calls of that width
+    b2, _ = dA.autotune(dX, reps=2)
+    assert dA.tuned[N] == b2
+    Y2 = dA.spmm(dX)
+    ok, worst = oracle.within_bound(Y2.cpu().numpy(), yref, bnd, TOL)
+    assert ok, worst
