@@ -192,7 +192,7 @@ int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t *rowptr, c
                                   void *workspace, dgsp_features_t *out, void *stream);
 
 /*
- * Profile-based selection (Section 3 describes running all kernels once off-line
+ * Profile-based selection (Section 3.1 names running all kernels once off-line
  * and keeping the fastest as the alternative to the rules): runs each of the four
  * kernels on the given buffers - one untimed call, then `reps` (clamped to
  * 1..100) calls bracketed by events on `stream` - and reports the fastest.

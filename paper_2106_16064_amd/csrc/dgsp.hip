@@ -190,20 +190,46 @@ int launch_rs_sr(const Problem& p) {
 }
 
 // ---------------------------------------------------------------- balanced launches
-// Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: the chunk size the
-// main kernel derives for `parts` chunks rounded to `quantum` items, cut into tiles of `tile` items.
-int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum, unsigned tile) {
+// Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: by the `parts` chunks
+// the main kernel derives (quanta of 2^quantum_log2 items), cut into tiles of 2^tile_log2 items
+// (tile_log2 < 0: not cut further).
+int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum_log2, int tile_log2) {
     const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum, tile);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2);
     return DGSP_OK;
 }
 
-// blocks of a machine-filling grid that shares nnz + M merge-path items in chunks of `chunk`
-inline unsigned balanced_blocks(const Problem& p, long long chunk, int blocks_per_cu) {
-    const long long cap = (long long)device_info().cus * blocks_per_cu;
+// Blocks of the grid that shares the nnz + M merge-path items of a balanced kernel, `tile` items per
+// tile.  The gathers of a CU go through one L1 whose capacity for outstanding misses bounds them,
+// whatever the number of waves, so CUs must finish together: the grid is a whole multiple of the CU
+// count (544 blocks on 256 CUs ran 25 % slower than 512).  A matrix too small for one tile per wave
+// on every CU gets one wave per tile.  Blocks per CU, at most what is resident:
+//   sequential kernel: as many as there are tiles for (its dense-row loads want every wave they can get);
+//   parallel kernel: one per 12 tiles per wave - a wave pays a start-up (a search in rowptr, loads
+//     that nothing overlaps yet) and fewer waves leave more of the L1 to each - but two as soon as
+//     that leaves a wave 6 tiles (measured on matrices of 1 M to 57 M entries).
+constexpr long long kNbPrTilesPerWave = 12;
+
+inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per_cu, bool parallel,
+                                long long col_blocks = 1) {
+    const long long cus = device_info().cus;
+    const long long cap = cus * blocks_per_cu;
     if (p.nnz < 0) return (unsigned)cap;
-    const long long chunks = (p.nnz + p.M + chunk - 1) / chunk;
-    return clamp_blocks((chunks + kWavesPerBlock - 1) / kWavesPerBlock, cap);
+    const long long tiles = (p.nnz + p.M + tile - 1) / tile;
+    const long long waves = cus * kWavesPerBlock;
+    if (tiles <= waves) return clamp_blocks((tiles + kWavesPerBlock - 1) / kWavesPerBlock, cap);
+    long long per_cu;
+    if (parallel) {
+        per_cu = tiles / (waves * kNbPrTilesPerWave);
+        if (per_cu < 2) per_cu = tiles >= waves * kNbPrTilesPerWave ? 2 : 1;
+    } else {
+        // the column blocks of a wide X (grid.y) are resident side by side: count them in
+        const long long want = (tiles * col_blocks + waves - 1) / waves;
+        if (col_blocks > 1 && want <= blocks_per_cu) return clamp_blocks(cus * want / col_blocks, cap);
+        per_cu = (tiles + waves - 1) / waves;
+    }
+    if (per_cu > blocks_per_cu) per_cu = blocks_per_cu;
+    return (unsigned)(cus * per_cu);
 }
 
 template <int V, int KQ>
@@ -212,9 +238,9 @@ int launch_nb_pr_v(const Problem& p) {
     const unsigned col_groups = (unsigned)(p.N / V);
     // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.N > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
-    const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>)), col_groups);
+    const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, kWave, 0)) return rc;
+        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
         DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
@@ -235,9 +261,9 @@ int launch_nb_sr_v(const Problem& p) {
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
-    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>)), col_blocks);
+    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 1u << logU, kNbSrTile)) return rc;
+        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
         DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;

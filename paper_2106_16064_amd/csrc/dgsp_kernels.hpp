@@ -304,13 +304,13 @@ __global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, cons
 // of a piece.  For matrices without empty stretches it is the paper's fixed
 // share of non-zeros up to the few percent that row markers add.
 //
-// The list is cut into kSubRanges * (number of resident waves) contiguous
-// chunks; wave w takes chunks w, w + nwaves, ... (waves of one XCD hold
-// neighbouring chunks).  Equal shares do not take equal time - the dense-matrix
-// gather of one region hits in cache, that of another does not - and dealing
-// each wave chunks from far-apart regions evens that out without any shared
-// counter (one contended atomic costs more than a tile on this machine).  A
-// wave finds the first row of a chunk with a 64-way search and then walks.
+// The list is cut into kSubRanges * (number of waves) contiguous chunks; wave w
+// takes chunks w, w + nwaves, ... (waves of one XCD hold neighbouring chunks).
+// Chunks begin at multiples of a quantum of items and differ by at most one
+// quantum: chunk c covers quanta [c*Q/parts, (c+1)*Q/parts) of the Q quanta, so
+// no wave stays without work while another holds two quanta.  The split is
+// static: one contended atomic costs more than a tile on this machine.  A wave
+// finds the first row of a chunk with a 64-way search and then walks.
 //
 // Rows whose items straddle a chunk boundary (in the sequential kernel: the
 // boundary of a lane group's run) are combined with fp32 atomic adds; the
@@ -321,23 +321,43 @@ __global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, cons
 
 constexpr unsigned kSubRanges = 1;
 
-// Items per chunk when `items` merge-path items are shared by `parts` chunks,
-// rounded up to a multiple of `quantum`.
-__device__ __forceinline__ unsigned merge_chunk_items(unsigned items, unsigned parts, unsigned quantum) {
-    unsigned per = items / parts + (items % parts != 0);
-    per = ((per + quantum - 1) / quantum) * quantum;
-    return per ? per : quantum;
-}
+// The even split of the Q quanta into `parts` chunks: chunk c starts at quantum floor(c * Q / parts),
+// so chunks differ by at most one quantum and the longer ones are spread over the whole list (put
+// first, they would all fall to the first XCDs).  The quotients are formed in fp64: numerators stay
+// below 2^53 and a non-integer quotient n / m lies at least 1 / m away from an integer, far more than
+// the rounding of one correctly rounded division, so the floors are exact - and much cheaper here
+// than 64-bit integer division, which the per-row test of the prepare kernel would pay twice.
+struct EvenSplit {
+    unsigned Q, parts, shift;     // quanta, chunks, log2 of the quantum
+    __device__ __forceinline__ EvenSplit(unsigned items, unsigned parts_, unsigned quantum_log2) {
+        const unsigned quantum = 1u << quantum_log2;
+        Q = (items >> quantum_log2) + ((items & (quantum - 1)) != 0);
+        parts = parts_;
+        shift = quantum_log2;
+    }
+    // first item of chunk c (c may be `parts`: the end of the list, rounded up to a quantum)
+    __device__ __forceinline__ unsigned start(unsigned c) const {
+        const double n = (double)((unsigned long long)c * Q);
+        return (unsigned)(n / (double)parts) << shift;
+    }
+    // chunk that holds item d: the largest c with floor(c * Q / parts) <= d's quantum
+    __device__ __forceinline__ unsigned chunk_of(unsigned d) const {
+        const unsigned long long q = d >> shift;
+        const double n = (double)((q + 1) * parts - 1);
+        return (unsigned)(n / (double)Q);
+    }
+};
 
 // Zeroes the rows whose items do not all lie in one piece of the partition.
 // unit > 0: pieces are the multiples of `unit` items.  unit == 0: pieces are
-// the chunks for `parts` chunks (see merge_chunk_items), cut further into
-// tiles of `tile` items counted from the chunk's start when tile > 0.
+// the `parts` chunks of the even split with quanta of 2^quantum_log2 items, cut
+// further into tiles of 2^tile_log2 items counted from the chunk's start when
+// tile_log2 >= 0.
 // One thread per row: split rows are few (at most two per piece), the test is
 // the cost.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
-                                                             unsigned quantum, unsigned tile) {
+                                                             unsigned quantum_log2, int tile_log2) {
     const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
     if (row >= M) return;
     const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
@@ -346,9 +366,13 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const 
     if (unit != 0) {
         if (first / unit == last / unit) return;
     } else {
-        const unsigned per = merge_chunk_items((unsigned)rowptr[M] + (unsigned)M, parts, quantum);
-        const unsigned c1 = first / per, c2 = last / per;
-        if (c1 == c2 && (tile == 0 || (first - c1 * per) / tile == (last - c1 * per) / tile)) return;
+        const EvenSplit split((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
+        const unsigned c1 = split.chunk_of(first), c2 = split.chunk_of(last);
+        if (c1 == c2) {
+            if (tile_log2 < 0) return;
+            const unsigned start = split.start(c1);
+            if ((first - start) >> tile_log2 == (last - start) >> tile_log2) return;
+        }
     }
     float* y = Y + (size_t)row * N;
     for (int n = 0; n < N; ++n) y[n] = 0.0f;
@@ -356,24 +380,24 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const 
 
 // The chunks of the calling wave: chunk(s) = s * nwaves + wave id, s < kSubRanges.
 struct ChunkPlan {
-    unsigned nnz, items, per, nwaves, gw;
+    unsigned nnz, items, nwaves, gw;
+    EvenSplit split;
+    __device__ __forceinline__ ChunkPlan(unsigned nnz_, unsigned items_, unsigned nwaves_, unsigned gw_,
+                                         unsigned quantum_log2)
+        : nnz(nnz_), items(items_), nwaves(nwaves_), gw(gw_), split(items_, nwaves_ * kSubRanges, quantum_log2) {}
     __device__ __forceinline__ bool range(unsigned s, unsigned& d0, unsigned& d1) const {
-        const unsigned long long a = (unsigned long long)(s * nwaves + gw) * per;
-        if (a >= items) return false;
-        d0 = (unsigned)a;
-        d1 = items - d0 > per ? d0 + per : items;
-        return true;
+        const unsigned c = s * nwaves + gw;
+        d0 = split.start(c);
+        const unsigned e = split.start(c + 1);
+        d1 = e < items ? e : items;
+        return d0 < d1;
     }
 };
 
-__device__ __forceinline__ ChunkPlan plan_chunks(const int* __restrict__ rowptr, int M, unsigned quantum) {
-    ChunkPlan p;
-    p.nnz = (unsigned)rowptr[M];
-    p.items = p.nnz + (unsigned)M;
-    p.nwaves = gridDim.x * kWavesPerBlock;
-    p.gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
-    p.per = merge_chunk_items(p.items, p.nwaves * kSubRanges, quantum);
-    return p;
+__device__ __forceinline__ ChunkPlan plan_chunks(const int* __restrict__ rowptr, int M, unsigned quantum_log2) {
+    const unsigned nnz = (unsigned)rowptr[M];
+    return ChunkPlan(nnz, nnz + (unsigned)M, gridDim.x * kWavesPerBlock,
+                     xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block(), quantum_log2);
 }
 
 // Number of rows whose end marker lies before diagonal d, i.e. rows r with
@@ -453,13 +477,13 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     float* buf = s_buf[wib];
     const int n0 = blockIdx.y * V;
 
-    const ChunkPlan plan = plan_chunks(rowptr, M, kWave);
+    const ChunkPlan plan = plan_chunks(rowptr, M, 6);        // quanta of one wave's width
     const unsigned nnz = plan.nnz;
     const unsigned long long y_elems = (unsigned long long)M * (unsigned)N;
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
     unsigned d0, d1;
-    if (!plan.range(sub, d0, d1)) break;
+    if (!plan.range(sub, d0, d1)) continue;
 
     if (nnz == 0) {
         // nothing stored: every item is a row end; my rows are [d0, d1)
@@ -732,7 +756,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const long long n = ((long long)blockIdx.y * G + gl) * V;
     const bool col_ok = n < N;
 
-    const ChunkPlan plan = plan_chunks(rowptr, M, U);     // chunks start at multiples of U: runs stay aligned
+    const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
     const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
@@ -741,7 +765,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
     unsigned d0, d1;
-    if (!plan.range(sub, d0, d1)) break;
+    if (!plan.range(sub, d0, d1)) continue;
     int is = wave_merge_rows_before(rowptr, M, d0, lane);
     unsigned js = d0 - (unsigned)is;
     for (unsigned ds = d0; ds < d1; ds += W) {
