@@ -448,59 +448,73 @@ def run_ablation(args):
     return 0
 
 
+THRESHOLD_NAMES = ("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min", "pr_nnz_max",
+                   "short_avg_row_max", "short_max_row_max")
+
+
 def run_fit(args):
-    """Grid-fits the selector thresholds on the seed-0 matrices of a finished sweep
-    (gpurun_out/bench_sweep.jsonl), checks them on the seed-1 matrices.  No GPU needed."""
+    """Grid-fits the selector thresholds.  Data: the seed-0 matrices of a finished sweep
+    (gpurun_out/bench_sweep.jsonl) plus, if that suite ran, the larger matrices of
+    gpurun_out/bench_size.jsonl (the sweep alone cannot place the size guard); checked on the
+    seed-1 matrices of the sweep.  No GPU needed."""
     path = args.out or os.path.join("gpurun_out", "bench_sweep.jsonl")
     rows = [json.loads(l) for l in open(path)]
-    for r in rows:
+    size_path = os.path.join(os.path.dirname(path) or ".", "bench_size.jsonl")
+    big = [json.loads(l) for l in open(size_path)] if os.path.exists(size_path) else []
+    for r in rows + big:
         r["stdv"] = r["avg_row"] * r["cv_row"]
+    inf = float("inf")
 
-    def choose(r, t, nnz_max=float("inf")):
-        npm, pr_avg, pr_cv, sr_cv, sr_std = t
+    def choose(r, t):
+        npm, pr_avg, pr_cv, sr_cv, sr_std, nnz_max, sh_avg, sh_max = t
         if r["N"] <= npm:
+            if r["avg_row"] <= sh_avg and r["max_row"] <= sh_max:
+                return "rs_sr"
             return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv and r["nnz"] < nnz_max) else "nb_pr"
         return "nb_sr" if (r["cv_row"] > sr_cv and r["stdv"] > sr_std) else "rs_sr"
 
     def loss(rs, t):
+        if not rs:
+            return 0.0, 0.0
         l = [r["ms"][choose(r, t)] / min(r["ms"].values()) - 1 for r in rs]
         return sum(l) / len(l), max(l)
 
     fit = [r for r in rows if r["matrix"].endswith("_s0")]
     test = [r for r in rows if r["matrix"].endswith("_s1")]
-    grid = [(npm, a, c, sc, ss) for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
-            for c in (0.3, 1.0, 2.0, 4.0, 1e30) for sc in (0.3, 0.8, 1.0, 1.5, 2.0, 3.5, 1e9) for ss in (0, 3, 10, 30, 60)]
-    best = min(grid, key=lambda t: loss(fit, t)[0])
-    paper = min((t for t in grid if t[0] == 4 and t[2] == 1e30 and t[4] == 0), key=lambda t: loss(fit, t)[0])
+    train = fit + big
+
+    # stage 1: the paper's tree (5 thresholds), added rules off; stage 2: the added rules on the 20 best trees
+    tree = [(npm, a, c, sc, ss) for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
+            for c in (0.05, 0.1, 0.2, 0.3, 0.5, 1.0, 2.0, 4.0, 1e30) for sc in (0.3, 0.8, 1.0, 1.5, 2.0, 3.5, 1e9)
+            for ss in (0, 3, 10, 30, 60)]
+    off = (inf, 0.0, 0)
+    ranked = sorted(tree, key=lambda t: loss(train, t + off)[0])
+    added = [(nm, a, m) for nm in (5e6, 1e7, 2e7, 4e7, inf) for (a, m) in
+             [(0.0, 0)] + [(a, m) for a in (5, 10, 20, 40) for m in (16, 32, 64, 128, 512)]]
+    best = min((t + x for t in ranked[:20] for x in added), key=lambda t: loss(train, t)[0])
+    paper = min((t + off for t in tree if t[0] == 4 and t[2] == 1e30 and t[4] == 0), key=lambda t: loss(fit, t)[0])
     single = {k: (sum(r["ms"][k] / min(r["ms"].values()) - 1 for r in rows) / len(rows)) for k in rows[0]["ms"]}
     per_n = {}
     for r in rows:
         per_n.setdefault(r["N"], []).append(r["ms"][choose(r, best)] / min(r["ms"].values()) - 1)
-    # the size guard of the parallel side: fitted on the larger matrices of `--suite size`, if that ran
-    size_fit = None
-    size_path = os.path.join(os.path.dirname(path) or ".", "bench_size.jsonl")
-    if os.path.exists(size_path):
-        big = [json.loads(l) for l in open(size_path)]
-        for r in big:
-            r["stdv"] = r["avg_row"] * r["cv_row"]
 
-        def size_loss(rs, nnz_max):
-            l = [r["ms"][choose(r, best, nnz_max)] / min(r["ms"].values()) - 1 for r in rs]
-            return sum(l) / len(l), max(l)
+    def variant(**kw):            # the fitted thresholds with some of the added rules switched off
+        t = dict(zip(THRESHOLD_NAMES, best))
+        t.update(kw)
+        t = tuple(t[k] for k in THRESHOLD_NAMES)
+        return {"sweep_fit": loss(fit, t)[0], "sweep_heldout": loss(test, t)[0], "size_cells": loss(big, t)[0]}
 
-        cands = (5e6, 1e7, 1.5e7, 2e7, 3e7, 4e7, float("inf"))
-        nm = min(cands, key=lambda c: size_loss(big + fit, c)[0])
-        size_fit = {"pr_nnz_max": nm, "cells": len(big),
-                    "mean_loss_size_cells": {str(c): size_loss(big, c)[0] for c in cands},
-                    "max_loss_size_cells": {str(c): size_loss(big, c)[1] for c in cands},
-                    "mean_loss_sweep_all": {str(c): size_loss(rows, c)[0] for c in cands}}
     print(json.dumps({
-        "suite": "fit", "cells": len(rows), "size_guard": size_fit,
-        "thresholds": dict(zip(("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min"), best)),
+        "suite": "fit", "sweep_cells": len(rows), "size_cells": len(big),
+        "thresholds": dict(zip(THRESHOLD_NAMES, best)),
         "mean_loss_fit_seed0": loss(fit, best)[0], "mean_loss_heldout_seed1": loss(test, best)[0],
-        "mean_loss_all": loss(rows, best)[0], "max_loss_all": loss(rows, best)[1],
-        "paper_shaped_tree": {"thresholds": paper, "mean_loss_fit": loss(fit, paper)[0],
-                              "mean_loss_heldout": loss(test, paper)[0]},
+        "mean_loss_sweep_all": loss(rows, best)[0], "max_loss_sweep_all": loss(rows, best)[1],
+        "mean_loss_size_cells": loss(big, best)[0], "max_loss_size_cells": loss(big, best)[1],
+        "added_rules_off": {"no_short_row_rule": variant(short_avg_row_max=0.0, short_max_row_max=0),
+                            "no_size_guard": variant(pr_nnz_max=inf),
+                            "neither": variant(short_avg_row_max=0.0, short_max_row_max=0, pr_nnz_max=inf)},
+        "paper_shaped_tree": {"thresholds": dict(zip(THRESHOLD_NAMES, paper)), "mean_loss_fit": loss(fit, paper)[0],
+                              "mean_loss_heldout": loss(test, paper)[0], "mean_loss_size_cells": loss(big, paper)[0]},
         "always_one_kernel_mean_loss": single,
         "mean_loss_per_N": {str(n): sum(v) / len(v) for n, v in sorted(per_n.items())}}))
     return 0

@@ -77,15 +77,22 @@ typedef struct {
  *   parallel:  avg_row >= pr_avg_row_min AND cv_row <= pr_cv_max AND
  *              nnz < pr_nnz_max -> row-split, else nnz-balanced (the last two
  *              conditions are additions: the paper's parallel-side rule looks at
- *              avg_row only.  The balanced kernel streams about a fifth faster
- *              but needs a second, small launch, which pays off from roughly
- *              2e7 stored entries on.  Set pr_cv_max to a huge value and
+ *              avg_row only.  The balanced kernel streams faster but needs a
+ *              second, small launch, which pays off from a few million stored
+ *              entries on.  Set pr_cv_max to a huge value and
  *              pr_nnz_max to INT64_MAX to get the paper's rule verbatim)
  *   sequential: cv_row > sr_cv_min AND stdv_row > sr_stdv_min -> nnz-balanced,
  *              else row-split (the paper's metric is cv_row alone; the second
  *              condition is an addition: with short rows even a large cv_row
  *              leaves no row long enough to stall a wave; set sr_stdv_min to 0
- *              for the paper's rule verbatim)                                  */
+ *              for the paper's rule verbatim)
+ *   short rows (an addition, checked first): N <= n_parallel_max AND
+ *              avg_row <= short_avg_row_max AND max_row <= short_max_row_max
+ *              -> row-split sequential.  At these widths that kernel gives every
+ *              row one lane; when all rows are short the whole wave is busy for
+ *              max_row steps with no cross-lane step, which beat both parallel
+ *              kernels on every such matrix measured.  Set short_avg_row_max
+ *              to 0 to switch it off.                                          */
 typedef struct {
     int64_t n_parallel_max;
     double pr_avg_row_min;
@@ -93,6 +100,8 @@ typedef struct {
     double sr_cv_min;
     double sr_stdv_min;
     int64_t pr_nnz_max;
+    double short_avg_row_max;
+    int64_t short_max_row_max;
 } dgsp_thresholds_t;
 
 /*

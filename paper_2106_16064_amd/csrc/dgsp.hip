@@ -288,10 +288,12 @@ int launch_nb_sr(const Problem& p) {
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
     /* pr_avg_row_min  */ 0.0,
-    /* pr_cv_max       */ 1.0,
+    /* pr_cv_max       */ 0.05,
     /* sr_cv_min       */ 0.3,
     /* sr_stdv_min     */ 3.0,
-    /* pr_nnz_max      */ 20000000,
+    /* pr_nnz_max      */ 5000000,
+    /* short_avg_row_max */ 20.0,
+    /* short_max_row_max */ 64,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
@@ -369,6 +371,8 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     if (!f || N < 1) return DGSP_AUTO;
     const dgsp_thresholds_t& t = g_thresholds;
     if (N <= t.n_parallel_max) {
+        // all rows short: one lane per row keeps a wave busy with no cross-lane step at all
+        if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
         // parallel reduction: long rows keep a row's lanes busy, short rows idle them
         const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max && f->nnz < t.pr_nnz_max;
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;

@@ -64,6 +64,7 @@ def feat(avg, cv, M=1000):
     f = dg.Features()
     f.M, f.K, f.nnz = M, M, int(avg * M)
     f.avg_row, f.stdv_row, f.cv_row = avg, avg * cv, cv
+    f.max_row = int(avg * (1 + 3 * cv)) + 1
     return f
 
 
@@ -72,7 +73,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62)      # the paper's rule verbatim (no added guards)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0)      # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -100,6 +101,14 @@ def test_selection_rules_follow_the_decision_tree():
         assert dg.dgsp_select_algo(feat(64, 0.1, M=1000), 1) == dg.NB_PR   # 64 000 entries: second launch pays
         assert dg.dgsp_select_algo(feat(64, 0.1, M=500), 1) == dg.RS_PR    # 32 000 entries
         assert dg.dgsp_select_algo(feat(64, 0.1, M=1000), 64) == dg.RS_SR  # sequential side unaffected
+        t.short_avg_row_max, t.short_max_row_max = 20.0, 64                # the added short-row rule
+        dg.dgsp_set_thresholds(t)
+        f = feat(4, 0.5); f.max_row = 16
+        assert dg.dgsp_select_algo(f, 2) == dg.RS_SR                       # every row short: one lane per row
+        f.max_row = 400
+        assert dg.dgsp_select_algo(f, 2) != dg.RS_SR                       # one long row: back to the tree
+        f = feat(40, 0.1); f.max_row = 50
+        assert dg.dgsp_select_algo(f, 2) != dg.RS_SR                       # rows not short on average
         L = dg.lib()
         assert L.dgsp_select_algo(None, 4) == dg.AUTO
         assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
