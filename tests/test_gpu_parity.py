@@ -454,3 +454,19 @@ def test_autotune_reports_the_fastest_kernel_and_leaves_the_product(dg, N):
     Y2 = dA.spmm(dX)
     ok, worst = oracle.within_bound(Y2.cpu().numpy(), yref, bnd, TOL)
     assert ok, worst
+
+
+def test_forty_million_rows_mostly_empty(dg):
+    """Row counts far beyond the entry count: the merge-path positions row + rowptr[row] approach
+    2^26 while almost every item is a row-end marker (exercises the partition arithmetic, the
+    64-row output batches and the prepare launch at a size no other test reaches)."""
+    M, K = 40_000_000, 1000
+    rng = np.random.default_rng(11)
+    lens = np.zeros(M, dtype=np.int64)
+    hot = rng.choice(M, size=200_000, replace=False)
+    lens[hot] = rng.integers(1, 9, size=hot.size)
+    lens[12_345_678] = 5000                       # one long row in the middle of nowhere
+    A = wl.csr_from_lens(np.minimum(lens, K), K, seed=12, name="forty_million_rows")
+    X = wl.dense_matrix(K, 1, "uniform", seed=3)
+    ref = oracle.spmm_ref(A.M, A.K, 1, A.rowptr, A.colidx, A.vals, X)
+    check(dg, A, X, algos=(0, 1, 2, 3), ref=ref)
