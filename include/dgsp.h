@@ -238,6 +238,22 @@ int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
                         const dgsp_features_t *features, void *stream);
 
 /*
+ * The same multiplication on strided views: row k of X starts at X + k*ldx, row i
+ * of Y at Y + i*ldy (in floats; ldx >= N and ldy >= N, else DGSP_ERR_INVALID_ARG).
+ * Only the N used columns of a row are read or written; what lies between rows is
+ * not touched.  This is what a column slice of a wider row-major matrix needs
+ * (the dense columns shared out between devices, or processed a slice at a time).
+ * The vector width of the dense-row accesses (Section 2.1.2) additionally needs
+ * ldx and ldy to be multiples of it.  algo may be DGSP_AUTO: with features the
+ * rules choose, without them the balanced kernel for the width.  Everything else
+ * as dgsp_spmm_csr_nnz; `features` may be NULL (host pointer otherwise).
+ */
+int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                     const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                     const float *X, int64_t ldx, float *Y, int64_t ldy, int algo,
+                     const dgsp_features_t *features, void *stream);
+
+/*
  * Measurement aid: the same multiplication with one of the paper's optimisations
  * switched off, for the comparisons of Sections 2.1.2 and 2.1.3.  Same arguments,
  * layouts, result and error behaviour as dgsp_spmm_csr_nnz; `switches` is a

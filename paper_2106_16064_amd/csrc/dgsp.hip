@@ -63,6 +63,7 @@ static_assert((1 << kNbSrLogTile) == kNbSrTile, "tile must be a power of two");
 
 struct Problem {
     int M, N;
+    int ldx, ldy;       // leading dimensions of X and Y in elements (>= N)
     long long K, nnz;   // nnz < 0: unknown on the host
     const int* rowptr; const int* colidx; const float* vals; const float* X; float* Y;
     hipStream_t stream;
@@ -72,7 +73,10 @@ struct Problem {
 };
 
 inline int vector_width(const Problem& p) {
-    return (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) ? 1 : widest_vector(p.N, p.X, p.Y);
+    if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return 1;
+    int v = widest_vector(p.N, p.X, p.Y);
+    while (v > 1 && (p.ldx % v != 0 || p.ldy % v != 0)) v >>= 1;     // every row must start aligned
+    return v;
 }
 
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
@@ -104,7 +108,7 @@ int resident_blocks_per_cu(K kernel) {
 // ---------------------------------------------------------------- row-split launches
 // X can be addressed with 32-bit byte offsets (through a buffer descriptor)
 inline bool x_fits_descriptor(const Problem& p) {
-    return (unsigned long long)p.K * (unsigned long long)p.N * 4ull <= 0xffffffffull;
+    return dense_bytes(p.K, p.ldx, p.N) <= 0xffffffffull;
 }
 
 template <int V, bool XBUF>
@@ -116,7 +120,7 @@ int launch_rs_pr_v(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));
-    DGSP_LAUNCH((rs_pr_kernel<V, XBUF>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    DGSP_LAUNCH((rs_pr_kernel<V, XBUF>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
@@ -151,7 +155,7 @@ int launch_rs_sr_v(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
-    DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
@@ -165,7 +169,7 @@ int launch_rs_sr_direct_v(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
-    DGSP_LAUNCH((rs_sr_direct_kernel<V>), grid, p.M, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    DGSP_LAUNCH((rs_sr_direct_kernel<V>), grid, p.M, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
@@ -195,7 +199,7 @@ int launch_rs_sr(const Problem& p) {
 // (tile_log2 < 0: not cut further).
 int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum_log2, int tile_log2) {
     const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.ldy, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2);
     return DGSP_OK;
 }
 
@@ -237,12 +241,12 @@ int launch_nb_pr_v(const Problem& p) {
     constexpr unsigned tile = kWave * 4 * KQ;
     const unsigned col_groups = (unsigned)(p.N / V);
     // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
-    if (col_groups > 65535u || p.N > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
+    if (col_groups > 65535u || p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
     return DGSP_OK;
 }
 
@@ -265,7 +269,7 @@ int launch_nb_sr_v(const Problem& p) {
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+        DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
 
@@ -298,19 +302,22 @@ dgsp_thresholds_t g_thresholds = {
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
         const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
-        double col_span = 0.0, int switches = 0) {
+        double col_span = 0.0, int switches = 0, int64_t ldx = -1, int64_t ldy = -1) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
+    if (ldx < 0) ldx = N;            // packed rows unless the caller says otherwise
+    if (ldy < 0) ldy = N;
+    if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
     if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return DGSP_OK;
     // int32 index range; a little headroom keeps position arithmetic simple
     const int64_t lim = (int64_t)INT32_MAX - 4096;
-    if (M > lim || K > lim || N > lim || nnz > lim) return DGSP_ERR_INVALID_ARG;
+    if (M > lim || K > lim || N > lim || nnz > lim || ldx > lim || ldy > lim) return DGSP_ERR_INVALID_ARG;
     if (!rowptr || !Y) return DGSP_ERR_INVALID_ARG;
     if (nnz > 0 && (!colidx || !vals || !X || K == 0)) return DGSP_ERR_INVALID_ARG;
 
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
-    Problem p{(int)M, (int)N, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span, switches};
+    Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span, switches};
     switch (algo) {
         case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
         case DGSP_RS_PR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_pr(p);
@@ -342,6 +349,16 @@ extern "C" int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase,
                features ? features->col_span : 0.0);
+}
+
+extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                const int32_t* colidx, const float* vals, const float* X, int64_t ldx, float* Y,
+                                int64_t ldy, int algo, const dgsp_features_t* features, void* stream) {
+    if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
+    if (features && nnz < 0) nnz = features->nnz;
+    if (algo == DGSP_AUTO && features && N >= 1) algo = dgsp_select_algo(features, N);
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
+               features ? features->col_span : 0.0, 0, ldx, ldy);
 }
 
 extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,

@@ -106,6 +106,12 @@ __device__ __forceinline__ float stream_load(const float* p) { return __builtin_
 constexpr unsigned kBufferFlags = 0x00020000u;      // raw 32-bit buffer descriptor, dword 3
 constexpr unsigned kOutOfRange = 0xffffffffu;
 
+// Bytes from the first element of a row-major matrix of `rows` rows, leading dimension `ld` and `cols`
+// used columns to the end of its last row (a strided view stops there, not at rows * ld).
+__host__ __device__ __forceinline__ unsigned long long dense_bytes(long long rows, long long ld, long long cols) {
+    return rows > 0 ? (unsigned long long)((rows - 1) * ld + cols) * 4ull : 0ull;
+}
+
 // Descriptor for `bytes` bytes starting at p (clamped to the 4 GB a descriptor can span).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, unsigned long long bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0,

@@ -40,7 +40,7 @@ __host__ __device__ __forceinline__ int pr_lanes_log2(long long nnz, long long M
 constexpr int kRsPrUnroll = 4;   // row groups a wave keeps in flight
 
 template <int V, bool XBUF>
-__global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -59,13 +59,13 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
     const unsigned rows_per_step = (unsigned)(U * rows_per_wave);
     const unsigned nsteps = ((unsigned)M + rows_per_step - 1) / rows_per_step;
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
-    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? (unsigned long long)K * (unsigned)N * 4ull : 0ull);
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? dense_bytes(K, ldx, N) : 0ull);
 
     auto fetch_dense = [&](unsigned c, bool ok, int n0, float (&x)[V]) {
         if constexpr (XBUF) {
-            buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + (unsigned)n0 * 4u : kOutOfRange, x);
+            buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + (unsigned)n0 * 4u : kOutOfRange, x);
         } else {
-            load_vec<V>(X + (size_t)c * N + n0, x);                      // c is 0 when switched off: a valid row
+            load_vec<V>(X + (size_t)c * ldx + n0, x);                      // c is 0 when switched off: a valid row
 #pragma unroll
             for (int i = 0; i < V; ++i) x[i] = ok ? x[i] : 0.0f;
         }
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
             for (int u = 0; u < U; ++u) {
                 segmented_scan<V>(acc[u], gl, lane, G);   // all 64 lanes arrive here together
                 const unsigned long long row = row0 + (unsigned)(u * rows_per_wave + g);
-                if (row < (unsigned long long)M && gl == G - 1) store_vec<V>(Y + (size_t)row * N + n0, acc[u]);
+                if (row < (unsigned long long)M && gl == G - 1) store_vec<V>(Y + (size_t)row * ldy + n0, acc[u]);
             }
         }
     }
@@ -162,7 +162,7 @@ constexpr int kRsSrTile = 512;   // cached pairs per wave and round
 // N = 8: 204 us at depth 4, 260 us at depth 1), and so do rows of uneven length.  The host picks.
 
 template <int V, bool XBUF, int DEPTH>
-__global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
     const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;
 
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
-    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const unsigned long long x_bytes = dense_bytes(K, ldx, N);
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? x_bytes : 0ull);
     const unsigned n_bytes = (unsigned)n * 4u;
 
@@ -231,9 +231,9 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
                         a[u] = ok ? cv[e] : 0.0f;
                         const unsigned c = (unsigned)cc[e];
                         if constexpr (XBUF) {
-                            buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + n_bytes : kOutOfRange, x[u]);
+                            buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
                         } else {
-                            load_vec<V>(X + (size_t)(ok ? c : 0u) * N + n, x[u]);
+                            load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + n, x[u]);
 #pragma unroll
                             for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
                         }
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
                 }
             }
         }
-        if (live && col_ok) store_vec<V>(Y + (size_t)row * N + n, acc);
+        if (live && col_ok) store_vec<V>(Y + (size_t)row * ldy + n, acc);
     }
 }
 
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
 // group reads colidx[p] and vals[p] itself, straight from memory, one entry after the other.
 // Kept for measurements only.
 template <int V>
-__global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                                const int* __restrict__ colidx,
                                                                const float* __restrict__ vals,
                                                                const float* __restrict__ X, float* __restrict__ Y,
@@ -280,11 +280,11 @@ __global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, cons
             const int c = colidx[p];
             const float a = vals[p];
             float x[V];
-            load_vec<V>(X + (size_t)c * N + n, x);
+            load_vec<V>(X + (size_t)c * ldx + n, x);
 #pragma unroll
             for (int i = 0; i < V; ++i) acc[i] = fmaf(a, x[i], acc[i]);
         }
-        store_vec<V>(Y + (size_t)row * N + n, acc);
+        store_vec<V>(Y + (size_t)row * ldy + n, acc);
     }
 }
 
@@ -355,7 +355,7 @@ struct EvenSplit {
 // tile_log2 >= 0.
 // One thread per row: split rows are few (at most two per piece), the test is
 // the cost.
-__global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ldy, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
                                                              unsigned quantum_log2, int tile_log2) {
     const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, const 
             if ((first - start) >> tile_log2 == (last - start) >> tile_log2) return;
         }
     }
-    float* y = Y + (size_t)row * N;
+    float* y = Y + (size_t)row * ldy;
     for (int n = 0; n < N; ++n) y[n] = 0.0f;
 }
 
@@ -463,7 +463,7 @@ constexpr unsigned kNoRow = 0xffffffffu;
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
 template <int V, int KQ>
-__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y) {
@@ -479,7 +479,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 
     const ChunkPlan plan = plan_chunks(rowptr, M, 6);        // quanta of one wave's width
     const unsigned nnz = plan.nnz;
-    const unsigned long long y_elems = (unsigned long long)M * (unsigned)N;
+    const unsigned long long y_elems = dense_bytes(M, ldy, N) / 4ull;
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
     unsigned d0, d1;
@@ -490,7 +490,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         float zero[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) zero[i] = 0.0f;
-        for (unsigned r = d0 + lane; r < d1; r += kWave) store_vec<V>(Y + (size_t)r * N + n0, zero);
+        for (unsigned r = d0 + lane; r < d1; r += kWave) store_vec<V>(Y + (size_t)r * ldy + n0, zero);
         continue;
     }
 
@@ -522,7 +522,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         start = t.x; end = t.y;
     };
     // the dense operand: byte offsets of X rows fit 32 bits unless X is 4 GB or more
-    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const unsigned long long x_bytes = dense_bytes(K, ldx, N);
     const bool x_small = x_bytes <= 0xffffffffull;
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
 
@@ -580,10 +580,10 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         if (x_small) {
 #pragma unroll
             for (int e = 0; e < E; ++e)
-                buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)N * 4u : kOutOfRange, x[e]);
+                buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e]);
         } else {
 #pragma unroll
-            for (int e = 0; e < E; ++e) load_vec<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * N + n0, x[e]);
+            for (int e = 0; e < E; ++e) load_vec<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * ldx + n0, x[e]);
         }
         {
             const bool more = d1 - ds > (unsigned)W;       // past the chunk's last tile the loads are switched off
@@ -667,7 +667,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         // ---- write the rows [is, ie) out, lane l row is + l: the first 64 with one unconditional
         //      buffer store, further batches (tiles crowded with short rows) in a loop
         {
-            const unsigned long long first_elem = (unsigned long long)is * (unsigned)N + (unsigned)n0;
+            const unsigned long long first_elem = (unsigned long long)is * (unsigned)ldy + (unsigned)n0;
             const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
             __amdgpu_buffer_rsrc_t yrows = __builtin_amdgcn_make_buffer_rsrc(
                 (void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left, kBufferFlags);
@@ -677,8 +677,8 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
                 load_vec<V>(buf + (size_t)t * V, val);
                 const bool live = t < nrows;
                 const bool shared = first_split && is + t == r_first;   // finished by an atomic add instead
-                buffer_store_vec<V>(yrows, (live && !shared) ? (unsigned)t * (unsigned)N * 4u : kOutOfRange, val);
-                if (live && shared) atomic_add_vec<V>(Y + (size_t)(is + t) * N + n0, val);
+                buffer_store_vec<V>(yrows, (live && !shared) ? (unsigned)t * (unsigned)ldy * 4u : kOutOfRange, val);
+                if (live && shared) atomic_add_vec<V>(Y + (size_t)(is + t) * ldy + n0, val);
             };
             write_rows(0);
             for (int k = 1; k * kWave < nrows; ++k) write_rows(k);
@@ -698,7 +698,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     bool any = false;
 #pragma unroll
     for (int i = 0; i < V; ++i) any |= carry[i] != 0.0f;
-    if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * N + n0, carry);
+    if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * ldy + n0, carry);
     }   // next chunk
 }
 
@@ -725,7 +725,7 @@ constexpr int kNbSrTile = 512;
 constexpr int kNbSrLogTile = 9;
 
 template <int V, bool XBUF, int DEPTH>
-__global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
-    const unsigned long long x_bytes = (unsigned long long)K * (unsigned)N * 4ull;
+    const unsigned long long x_bytes = dense_bytes(K, ldx, N);
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? x_bytes : 0ull);
     const unsigned n_bytes = (unsigned)n * 4u;
 
@@ -842,7 +842,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
             auto flush_rows_ending_at = [&](unsigned pos) {
                 while (next_end == pos && t < t_end) {
                     if (cur_first < dg) to_slot(true);
-                    else store_vec<V>(Y + (size_t)((long long)is + t) * N + n, acc);
+                    else store_vec<V>(Y + (size_t)((long long)is + t) * ldy + n, acc);
 #pragma unroll
                     for (int i = 0; i < V; ++i) acc[i] = 0.0f;
                     cur_first = (unsigned)(is + t) + 1 + next_end;      // the next row starts right after this end marker
@@ -860,9 +860,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                     a[u] = ok ? cv[e] : 0.0f;
                     const unsigned c = (unsigned)cc[e];
                     if constexpr (XBUF) {
-                        buffer_load_vec<V>(rx, ok ? c * (unsigned)N * 4u + n_bytes : kOutOfRange, x[u]);
+                        buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
                     } else {
-                        load_vec<V>(X + (size_t)(ok ? c : 0u) * N + n, x[u]);
+                        load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + n, x[u]);
 #pragma unroll
                         for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
                     }
@@ -890,7 +890,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                 if (row >= 0) {
                     float val[V];
                     load_vec<V>(slot_acc + (size_t)(s * G + gl) * V, val);
-                    float* y = Y + (size_t)row * N + n;
+                    float* y = Y + (size_t)row * ldy + n;
                     // started inside the tile (s > 0) and ended inside it: nobody else has a part of this row
                     if (s > 0 && slot_end[s]) store_vec<V>(y, val); else atomic_add_vec<V>(y, val);
                 }

@@ -470,3 +470,48 @@ def test_forty_million_rows_mostly_empty(dg):
     X = wl.dense_matrix(K, 1, "uniform", seed=3)
     ref = oracle.spmm_ref(A.M, A.K, 1, A.rowptr, A.colidx, A.vals, X)
     check(dg, A, X, algos=(0, 1, 2, 3), ref=ref)
+
+
+# ------------------------------------------------------------------ strided views (leading dimensions)
+@pytest.mark.parametrize("N,ldx,ldy,x0,y0", [
+    (1, 8, 4, 0, 0), (1, 7, 3, 5, 2), (2, 8, 8, 2, 4), (2, 9, 5, 1, 3), (4, 16, 8, 4, 4), (4, 12, 12, 3, 0),
+    (8, 128, 64, 32, 8), (32, 128, 128, 64, 96), (33, 70, 40, 1, 7), (100, 260, 104, 4, 0), (64, 64, 64, 0, 0),
+])
+def test_column_slices_of_wider_matrices(dg, N, ldx, ldy, x0, y0):
+    """Y[:, y0:y0+N] = A X[:, x0:x0+N] on views of row-major matrices with ldx / ldy floats per row:
+    the product equals the oracle's on the packed copy, and nothing outside the slice is written."""
+    import torch
+    A = wl.sweep_csr(2500, 12, "lognormal", seed=N + ldx)
+    rng = np.random.default_rng(N * 1000 + ldx)
+    Xw = rng.standard_normal((A.K, ldx)).astype(np.float32)
+    Xs = np.ascontiguousarray(Xw[:, x0:x0 + N])
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, Xs)
+    dA = dg.DeviceCsr(A)
+    dXw = torch.from_numpy(Xw).cuda()
+    for algo in (0, 1, 2, 3, dg.AUTO):
+        print(f"[case] strided N={N} ldx={ldx} ldy={ldy} x0={x0} y0={y0} algo={algo}", flush=True)
+        dYw = torch.full((A.M, ldy), float("nan"), dtype=torch.float32, device="cuda:0")
+        dg.dgsp_spmm_csr_ld(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dXw[:, x0:x0 + N],
+                            dYw[:, y0:y0 + N], algo, dA.features)
+        torch.cuda.synchronize()
+        Yw = dYw.cpu().numpy()
+        Y = Yw[:, y0:y0 + N]
+        assert not np.isnan(Y).any()
+        ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+        assert ok, f"algo {algo}: worst |err|/bound = {worst:.3e}"
+        outside = np.ones(ldy, dtype=bool); outside[y0:y0 + N] = False
+        assert np.isnan(Yw[:, outside]).all(), "wrote outside the slice"
+
+
+def test_leading_dimensions_smaller_than_the_width_are_rejected(dg):
+    import torch
+    A = wl.poisson_csr(64, 64, 4.0, seed=0)
+    dA = dg.DeviceCsr(A)
+    X = torch.zeros((A.K, 8), device="cuda:0")
+    Y = torch.zeros((A.M, 8), device="cuda:0")
+    L = dg.lib()
+    base = (A.M, A.K, 8, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr())
+    assert L.dgsp_spmm_csr_ld(*base, X.data_ptr(), 7, Y.data_ptr(), 8, dg.NB_SR, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ld(*base, X.data_ptr(), 8, Y.data_ptr(), 4, dg.NB_SR, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ld(*base, X.data_ptr(), 8, Y.data_ptr(), 8, dg.NB_SR, None, None) == dg.OK
+    torch.cuda.synchronize()
