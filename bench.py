@@ -42,7 +42,7 @@ CACHE_BYTES = 256e6 + 32e6     # Infinity Cache + 8 x 4 MB L2: what rotation has
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on dgsp_copy_f32);
 # see profiles/.  None = not measured for that cell.
 MEASURED_TRAFFIC_BYTES = {
-    "nb_pr/rmat_spmv/N1": 190.0e6,   # profiles/nb_pr_kernel_rmat20_spmv.md: 184.9 MB fetched + 5.1 MB written
+    "nb_pr/rmat_spmv/N1": 186.8e6,   # profiles/nb_pr_kernel_rmat20_spmv.md: 181.8 MB fetched + 5.0 MB written
 }
 
 
