@@ -19,6 +19,7 @@ prints one JSON line and writes details under gpurun_out/):
     --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
     --suite size      all four kernels on banded and random matrices of growing size, N <= 8
     --suite ablation  each optimisation against the kernel without it, on 27 R-MAT matrices
+    --suite tiny      the launch-bound 4096^2 configuration, eager launches against HIP graph replay
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
 """
 from __future__ import annotations
@@ -357,6 +358,47 @@ def run_sweep(args):
     return 0
 
 
+def run_tiny(args):
+    """The tiny configuration (4096^2, Poisson(8) rows, N = 4) is launch-bound: time per call of each
+    kernel launched eagerly and replayed from a HIP graph that holds 20 calls."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    A, X, label = make_workload("tiny", 4)
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    dY = torch.empty((A.M, 4), dtype=torch.float32, device="cuda:0")
+    out = {}
+    per_graph = 20
+    side = torch.cuda.Stream()
+    for algo in dg.ALGOS:
+        name = dg.dgsp_algo_name(algo)
+        with torch.cuda.stream(side):
+            for _ in range(5):
+                dA.spmm(dX, algo=algo, Y=dY)
+            side.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                dA.spmm(dX, algo=algo, Y=dY)
+            side.synchronize()
+            eager = (time.perf_counter() - t0) / args.steps
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(per_graph):
+                dA.spmm(dX, algo=algo, Y=dY)
+        graph.replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // per_graph)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        replay = (time.perf_counter() - t0) / (reps * per_graph)
+        out[name] = {"eager_us": eager * 1e6, "graph_us": replay * 1e6}
+    sel = dg.dgsp_algo_name(dg.dgsp_select_algo(dA.features, 4))
+    print(json.dumps({"suite": "tiny", "workload": label, "nnz": A.nnz, "selected": sel, "per_call": out}))
+    return 0
+
+
 def run_size(args):
     """All four kernels on banded and random matrices of growing size at small N: where the
     second launch of the balanced kernels starts to pay (fits the selector's pr_nnz_max)."""
@@ -545,7 +587,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "kernel", "fit"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -567,7 +609,7 @@ def main():
     from paper_2106_16064_amd import binding as dg
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
-            "ablation": run_ablation, "kernel": run_kernel}[args.suite](args)
+            "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel}[args.suite](args)
 
 
 if __name__ == "__main__":

@@ -515,3 +515,33 @@ def test_leading_dimensions_smaller_than_the_width_are_rejected(dg):
     assert L.dgsp_spmm_csr_ld(*base, X.data_ptr(), 8, Y.data_ptr(), 4, dg.NB_SR, None, None) == dg.ERR_INVALID_ARG
     assert L.dgsp_spmm_csr_ld(*base, X.data_ptr(), 8, Y.data_ptr(), 8, dg.NB_SR, None, None) == dg.OK
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("algo", [0, 1, 2, 3])
+def test_calls_can_be_captured_in_a_graph_and_replayed(dg, algo):
+    """The library allocates nothing and only launches kernels, so a call can be recorded into a HIP
+    graph.  Every replay is checked against the oracle, with eager work and new inputs in between."""
+    import torch
+    A = wl.poisson_csr(4096, 4096, 8.0, seed=3)
+    N = 4
+    dA = dg.DeviceCsr(A)
+    dX = torch.zeros((A.K, N), dtype=torch.float32, device="cuda:0")
+    dY = torch.zeros((A.M, N), dtype=torch.float32, device="cuda:0")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                     # one eager call first: fills the library's host-side caches
+        dA.spmm(dX, algo=algo, Y=dY)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dA.spmm(dX, algo=algo, Y=dY)                  # recorded on the capturing stream
+    for rep in range(3):
+        X = wl.dense_matrix(A.K, N, "uniform", seed=100 + rep)
+        dX.copy_(torch.from_numpy(X))
+        dY.fill_(float("nan"))                        # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+        assert ok, f"replay {rep}: worst |err|/bound = {worst:.3e}"
