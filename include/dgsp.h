@@ -22,10 +22,12 @@
  *     agree with an exact sum to within c*eps32*(|A||X|) elementwise, not bit
  *     for bit; the nnz-balanced kernels combine partial rows with fp32 atomic
  *     adds and are not run-to-run bit-reproducible.
- *   - X and Y are row-major with leading dimension N (the layout Section 2.1.2
- *     needs: X[k,0], X[k,1] adjacent).
- *   - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t
- *     passed as void*, NULL = the default stream) and the call returns.
+ *   - X and Y are row-major (the layout Section 2.1.2 needs: X[k,0], X[k,1]
+ *     adjacent) with leading dimension N unless an entry point takes ldx, ldy.
+ *   - Calls are asynchronous unless stated otherwise: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     the call returns.  dgsp_features_from_csr_device and dgsp_autotune wait
+ *     for their work because they hand results back in host memory.
  *   - Return value: a dgsp_status_t.  On any error nothing has been enqueued.
  */
 #ifndef DGSP_H

@@ -6,8 +6,10 @@
 //     (DPP moves or wave-private LDS), so there is no s_barrier anywhere.
 //   * `V` (1, 2 or 4) is the vector width of dense-row accesses: one
 //     dword / dwordx2 / dwordx4 per lane (vector-type dense-row loading,
-//     Section 2.1.2).  The host picks the widest V that divides N and matches
-//     the alignment of X and Y.
+//     Section 2.1.2).  The host picks the widest V that divides N, ldx and
+//     ldy and matches the alignment of X and Y.
+//   * X and Y are row-major with leading dimensions ldx, ldy (floats per row,
+//     >= N); only the N used columns of a row are touched.
 //   * Grids are sized to the machine, not to the matrix: a wave walks a list
 //     of row groups (row-split) or tiles (balanced).  That is what allows the
 //     number of stored entries to be read on the device from rowptr[M].
@@ -454,12 +456,12 @@ constexpr unsigned kNoRow = 0xffffffffu;
 //   6. The sum still open at the end of a tile is handed to the chunk's next
 //      tile in a register; only the two ends of a chunk can need an atomic add.
 //
-// Memory operations inside the tile loop are unconditional: loads clamp their
-// index and mask the value afterwards, the row store is a buffer store whose
-// offset is pushed out of range for lanes that have nothing to write (the
-// buffer unit drops those).  With no branch around them the outstanding-
-// operation counter can be waited on exactly, which is what lets the next
-// tile's loads stay in flight while this tile is reduced.
+// Memory operations inside the tile loop are unconditional: loads and the row
+// store go through buffer descriptors, and a lane that has nothing to load or
+// write pushes its offset out of range (the buffer unit returns zero / drops
+// the store and touches no memory).  With no branch around them the
+// outstanding-operation counter can be waited on exactly, which is what lets
+// the next tile's loads stay in flight while this tile is reduced.
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
 template <int V, int KQ>
