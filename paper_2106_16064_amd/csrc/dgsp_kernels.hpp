@@ -355,29 +355,47 @@ struct EvenSplit {
 // the `parts` chunks of the even split with quanta of 2^quantum_log2 items, cut
 // further into tiles of 2^tile_log2 items counted from the chunk's start when
 // tile_log2 >= 0.
-// One thread per row: split rows are few (at most two per piece), the test is
-// the cost.
+// One thread per row for the test (split rows are few: at most two per piece);
+// a wave then clears its split rows together, 64 columns per store.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ldy, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
                                                              unsigned quantum_log2, int tile_log2) {
     const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
-    if (row >= M) return;
-    const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
-    const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
-    if (first == last) return;                                           // an empty row is a single item
-    if (unit != 0) {
-        if (first / unit == last / unit) return;
-    } else {
-        const EvenSplit split((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
-        const unsigned c1 = split.chunk_of(first), c2 = split.chunk_of(last);
-        if (c1 == c2) {
-            if (tile_log2 < 0) return;
-            const unsigned start = split.start(c1);
-            if ((first - start) >> tile_log2 == (last - start) >> tile_log2) return;
+    bool split = false;
+    if (row < M) {
+        const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
+        const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
+        if (first != last) {                                                 // an empty row is a single item
+            if (unit != 0) {
+                split = first / unit != last / unit;
+            } else {
+                const EvenSplit es((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
+                const unsigned c1 = es.chunk_of(first), c2 = es.chunk_of(last);
+                split = c1 != c2;
+                if (!split && tile_log2 >= 0) {
+                    const unsigned start = es.start(c1);
+                    split = (first - start) >> tile_log2 != (last - start) >> tile_log2;
+                }
+            }
         }
     }
-    float* y = Y + (size_t)row * ldy;
-    for (int n = 0; n < N; ++n) y[n] = 0.0f;
+    if (N <= 8) {                                      // narrow rows: the thread clears its own
+        if (split) {
+            float* y = Y + (size_t)row * ldy;
+            for (int n = 0; n < N; ++n) y[n] = 0.0f;
+        }
+        return;
+    }
+    // the wave zeroes its split rows together: lane l clears columns l, l + 64, ...
+    const int lane = lane_id();
+    const long long row0 = row - lane;
+    unsigned long long todo = __ballot(split);
+    while (todo) {                                                           // wave-uniform
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        float* y = Y + (size_t)(row0 + src) * ldy;
+        for (int n = lane; n < N; n += kWave) y[n] = 0.0f;
+    }
 }
 
 // The chunks of the calling wave: chunk(s) = s * nwaves + wave id, s < kSubRanges.
@@ -760,6 +778,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 
     const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
+    const unsigned long long y_elems = dense_bytes(M, ldy, N) / 4ull;
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)
     const unsigned long long x_bytes = dense_bytes(K, ldx, N);
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X, XBUF ? x_bytes : 0ull);
@@ -791,26 +810,79 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
         for (int k = 0; k < kSlotFloats / kWave; ++k) slot_acc[k * kWave + lane] = 0.0f;
         slot_row[lane] = -1; slot_end[lane] = 0;
         if (lane == 0) { slot_row[kWave] = -1; slot_end[kWave] = 0; }
-        // end offsets of rows is, is+1, ... while their end marker is inside the tile
+        // end offsets of rows is, is+1, ... while their end marker is inside the tile: 64 candidates first,
+        // and if all of them end here (a tile crowded with short or empty rows) the other 448 in one go
         int ie = is;
-        for (int m = 0; m < W / kWave; ++m) {
-            const long long r = (long long)is + m * kWave + lane;
-            bool in = false;
-            if (r < M) {
-                const unsigned e = (unsigned)rowptr[r + 1];
-                in = (unsigned)r + e < de;
+        {
+            const unsigned long long rbytes = is < M ? (unsigned long long)(M + 1 - is) * 4ull : 0ull;
+            const __amdgpu_buffer_rsrc_t rr = make_buffer(rowptr + is, rbytes);     // rows past the last read as 0
+            auto take = [&](int m, unsigned e) {
+                const long long r = (long long)is + m * kWave + lane;
+                const bool in = r < M && (unsigned)r + e < de;
                 if (in) ends[m * kWave + lane] = (unsigned short)(e - js);
-            }
-            const int cnt = __popcll(__ballot(in));
+                return (int)__popcll(__ballot(in));
+            };
+            int cnt = take(0, (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rr, (unsigned)(lane + 1) * 4u, 0, 0));
             ie += cnt;
-            if (cnt < kWave) break;
+            if (cnt == kWave) {
+                unsigned e[W / kWave - 1];
+#pragma unroll
+                for (int m = 1; m < W / kWave; ++m)
+                    e[m - 1] = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rr, (unsigned)(m * kWave + lane + 1) * 4u, 0, 0);
+#pragma unroll
+                for (int m = 1; m < W / kWave; ++m) {
+                    if (cnt == kWave) { cnt = take(m, e[m - 1]); ie += cnt; }
+                }
+            }
         }
         const int nrows = ie - is;              // rows ending in this tile
         const unsigned rs_first = is < M ? (unsigned)rowptr[is] : nnz;   // start offset of row `is`
         wave_lds_sync();
 
-        const unsigned dg = ds + ((unsigned)g << logU);   // my run: diagonals [dg, dh)
-        if (dg < de && col_ok) {
+        // rows [is, ie) end in this tile; their results leave through one descriptor based at row `is`
+        const unsigned long long first_elem = (unsigned long long)is * (unsigned)ldy;
+        const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t yrows = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left, kBufferFlags);
+
+        // rows without entries get their zeros here, all groups together (group g: local rows g, g + groups, ...),
+        // so that the walk below meets a store only where a row with entries ends
+        {
+            float zero[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+            for (int t0 = 0; t0 < nrows; t0 += 4 * groups) {      // wave-uniform; four independent stores per round
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int tz = t0 + q * groups + g;
+                    bool empty = false;
+                    if (tz < nrows) {
+                        const int end = (int)ends[tz];
+                        const int start = tz == 0 ? (int)(rs_first - js) : (int)ends[tz - 1];   // negative: began before the tile
+                        empty = end == start;
+                    }
+                    buffer_store_vec<V>(yrows, (empty && col_ok) ? (unsigned)tz * (unsigned)ldy * 4u + n_bytes : kOutOfRange, zero);
+                }
+            }
+        }
+
+        // first local row in [lo, hi) whose end offset lies beyond `off` (end offsets never decrease); hi if none
+        auto first_row_ending_after = [&](int lo, int hi, unsigned off) {
+            if (lo >= hi || js + ends[lo] > off) return lo;          // the usual case: the next row has entries
+            ++lo;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (js + ends[mid] <= off) lo = mid + 1; else hi = mid;
+            }
+            return lo;
+        };
+
+        // ---- my run: diagonals [dg, dh) = entries [j, j_end) and the end markers of rows [t, t_end)
+        const unsigned dg = ds + ((unsigned)g << logU);
+        const bool has_run = dg < de && col_ok;
+        int t = 0, t_end = 0;
+        unsigned j = 0, j_end = 0, next_end = kNoRow, cur_first = 0;
+        if (has_run) {
             const unsigned dh = (de - dg > U) ? dg + U : de;
             // rows (local index t, row is+t) whose end marker lies before a diagonal d: is+t + ends[t] < d
             auto rows_before = [&](unsigned d) {
@@ -821,68 +893,79 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                 }
                 return lo;
             };
-            int t = rows_before(dg);                         // first row (local) to end at or after dg
-            const int t_end = rows_before(dh);               // rows [t, t_end) end inside my run
-            const unsigned j = dg - (unsigned)(is + t);      // first entry of my run
-            const unsigned j_end = dh - (unsigned)(is + t_end);
-            unsigned next_end = t < nrows ? js + ends[t] : kNoRow;   // end offset of the current row
-            // first item of the current row (its start offset is the previous row's end)
-            unsigned cur_first = (unsigned)(is + t) + (t == 0 ? rs_first : js + ends[t - 1]);
+            t = rows_before(dg);                             // first row (local) to end at or after dg
+            t_end = rows_before(dh);                         // rows [t, t_end) end inside my run
+            j = dg - (unsigned)(is + t);                     // first entry of my run
+            j_end = dh - (unsigned)(is + t_end);
+            // rows without entries at the head of the run are done already
+            const unsigned start_off = t == 0 ? rs_first : js + ends[t - 1];   // where row t's entries begin
+            t = first_row_ending_after(t, t_end, start_off);
+            next_end = t < nrows ? js + ends[t] : kNoRow;    // end offset of the current row
+            cur_first = (unsigned)(is + t) + start_off;      // first item of the current row
+        }
+        // lanes without a run keep j == j_end and t == t_end: they issue the same instructions, switched off
 
-            float acc[V];
+        float acc[V];
 #pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+        for (int i = 0; i < V; ++i) acc[i] = 0.0f;
 
-            // a partial sum of row is+t (it crosses my run's ends) goes to the slot of the run it started in
-            auto to_slot = [&](bool ended) {
-                const int s = cur_first < ds ? 0 : (int)((cur_first - ds) >> logU) + 1;
-                float* dst = slot_acc + (size_t)(s * G + gl) * V;
+        // a partial sum of row is+t (it crosses my run's ends) goes to the slot of the run it started in
+        auto to_slot = [&](bool ended) {
+            const int s = cur_first < ds ? 0 : (int)((cur_first - ds) >> logU) + 1;
+            float* dst = slot_acc + (size_t)(s * G + gl) * V;
 #pragma unroll
-                for (int i = 0; i < V; ++i) atomicAdd(dst + i, acc[i]);
-                if (gl == 0) { slot_row[s] = is + t; if (ended) slot_end[s] = 1; }   // every writer of slot_row[s] writes the same row
-            };
-            auto flush_rows_ending_at = [&](unsigned pos) {
-                while (next_end == pos && t < t_end) {
-                    if (cur_first < dg) to_slot(true);
-                    else store_vec<V>(Y + (size_t)((long long)is + t) * ldy + n, acc);
+            for (int i = 0; i < V; ++i) atomicAdd(dst + i, acc[i]);
+            if (gl == 0) { slot_row[s] = is + t; if (ended) slot_end[s] = 1; }   // every writer of slot_row[s] writes the same row
+        };
+        // The current row ends here (closing: its end marker lies in my run).  A row that began inside my run is
+        // stored, one that began earlier goes to its slot.  The store is issued by the whole wave whenever any
+        // group closes a row - switched off where none does - so no memory operation sits in a divergent branch.
+        auto close_row = [&](bool closing) {
+            if (__ballot(closing) != 0ull) {                 // wave-uniform
+                const bool direct = closing && cur_first >= dg;
+                buffer_store_vec<V>(yrows, direct ? (unsigned)t * (unsigned)ldy * 4u + n_bytes : kOutOfRange, acc);
+                if (closing) {
+                    if (!direct) to_slot(true);
 #pragma unroll
                     for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-                    cur_first = (unsigned)(is + t) + 1 + next_end;      // the next row starts right after this end marker
-                    ++t;
+                    const unsigned off = next_end;           // the next row's entries begin where this one's end
+                    t = first_row_ending_after(t + 1, t_end, off);   // rows without entries: zeros written above
+                    cur_first = (unsigned)(is + t) + off;
                     next_end = t < nrows ? js + ends[t] : kNoRow;
                 }
-            };
-
-            for (unsigned p0 = j; p0 < j_end; p0 += DEPTH) {
-                float x[DEPTH][V]; float a[DEPTH];
-#pragma unroll
-                for (int u = 0; u < DEPTH; ++u) {
-                    const bool ok = p0 + u < j_end;
-                    const int e = ok ? (int)(p0 + u - js) : 0;
-                    a[u] = ok ? cv[e] : 0.0f;
-                    const unsigned c = (unsigned)cc[e];
-                    if constexpr (XBUF) {
-                        buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
-                    } else {
-                        load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + n, x[u]);
-#pragma unroll
-                        for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < DEPTH; ++u) {
-                    const unsigned p = p0 + u;
-                    if (p < j_end) {
-                        flush_rows_ending_at(p);             // rows that end before entry p
-#pragma unroll
-                        for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);
-                    }
-                }
             }
-            flush_rows_ending_at(j_end);                     // rows whose end marker closes my run
-            // what is left belongs to a row that goes on after my run (if the run held entries of it)
-            if ((unsigned)(is + t) + j_end > cur_first) to_slot(false);
+        };
+        // the dense-row load of entry p into register set u; switched off past the run's last entry
+        float x[DEPTH][V]; float a[DEPTH];
+        auto issue = [&](int u, unsigned p) {
+            const bool ok = p < j_end;
+            const int e = ok ? (int)(p - js) : 0;
+            a[u] = ok ? cv[e] : 0.0f;
+            const unsigned c = (unsigned)cc[e];
+            if constexpr (XBUF) {
+                buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
+            } else {
+                load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + (col_ok ? n : 0), x[u]);
+#pragma unroll
+                for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
+            }
+        };
+        // DEPTH loads stay in flight: entry p is consumed while entry p + DEPTH is requested
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) issue(u, j + u);
+        for (unsigned p0 = j; __ballot(p0 < j_end) != 0ull; p0 += DEPTH) {     // the same trip count for every lane
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                const unsigned p = p0 + u;
+                close_row(p < j_end && next_end == p);       // the row before entry p is complete
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(a[u], x[u][i], acc[i]);   // a is 0 past the end
+                issue(u, p + DEPTH);
+            }
         }
+        close_row(t < t_end);                                // the row whose end marker follows my last entry
+        // what is left belongs to a row that goes on after my run (if the run held entries of it)
+        if (has_run && (unsigned)(is + t) + j_end > cur_first) to_slot(false);
         wave_lds_sync();                                     // every run has added its parts
 
         // one group per slot writes the rows that crossed run boundaries: slot g+1 by group g, slot 0 by group 0 too
