@@ -77,3 +77,14 @@ def test_stencil(dg, stencil128, N):
         dA = dg.DeviceCsr(ones)
         Y = dA.spmm(torch.ones((ones.K, 1), device="cuda:0"), algo=3).cpu().numpy()[:, 0]
         assert np.array_equal(Y, ones.row_lengths().astype(np.float32)) and Y.astype(np.float64).sum() == (3 * 128 - 2) ** 3
+
+
+@pytest.mark.parametrize("dist", wl.SWEEP_DISTS)
+@pytest.mark.parametrize("mean,N", [(64, 1), (64, 32), (16, 4), (4, 512)])
+def test_selector_sweep_matrices_at_full_size(dg, dist, mean, N):
+    """The sweep's matrices (2^18 rows, four row-length laws) at their real size: every kernel and
+    the adaptive call, elementwise against the oracle.  Row-split kernels are left out where one
+    very long row would make them take tens of milliseconds for no extra coverage."""
+    A = wl.sweep_csr(1 << 18, mean, dist, seed=1)
+    heavy = A.row_lengths().max() > 2000
+    run_cell(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=N), (-1, 2, 3) if heavy else (-1, 0, 1, 2, 3))
