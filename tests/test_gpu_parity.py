@@ -545,3 +545,34 @@ def test_calls_can_be_captured_in_a_graph_and_replayed(dg, algo):
         yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
         ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
         assert ok, f"replay {rep}: worst |err|/bound = {worst:.3e}"
+
+
+# ------------------------------------------------------------------ differentiable wrapper
+@pytest.mark.parametrize("N", [1, 4, 32])
+def test_gradient_with_respect_to_the_dense_operand(dg, N):
+    """Y = A X as an autograd operation: the forward product and dL/dX = A^T dL/dY both equal the
+    oracle's products (the second on the transposed arrays) within the same bound."""
+    import torch
+    from paper_2106_16064_amd.autograd import SparseOperator, transpose_csr
+    A = wl.rmat_csr(scale=13, avg_degree=12, seed=9)
+    op = SparseOperator(A)
+    X = wl.dense_matrix(A.K, N, "normal", seed=1)
+    Gy = wl.dense_matrix(A.M, N, "uniform", seed=2)
+    dX = torch.from_numpy(X).cuda().requires_grad_(True)
+    Y = op(dX)
+    Y.backward(torch.from_numpy(Gy).cuda())
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    ok, worst = oracle.within_bound(Y.detach().cpu().numpy(), yref, bnd, TOL)
+    assert ok, worst
+    T = transpose_csr(A)
+    gref, gbnd = oracle.spmm_ref(T.M, T.K, N, T.rowptr, T.colidx, T.vals, Gy)
+    ok, worst = oracle.within_bound(dX.grad.cpu().numpy(), gref, gbnd, TOL)
+    assert ok, worst
+    # a vector operand (SpMV) goes through the same path
+    if N == 1:
+        v = torch.from_numpy(X[:, 0].copy()).cuda().requires_grad_(True)
+        y = op(v)
+        y.sum().backward()
+        gref1, gbnd1 = oracle.spmm_ref(T.M, T.K, 1, T.rowptr, T.colidx, T.vals, np.ones((A.M, 1), dtype=np.float32))
+        ok, worst = oracle.within_bound(v.grad.cpu().numpy().reshape(-1, 1), gref1, gbnd1, TOL)
+        assert ok, worst

@@ -92,3 +92,25 @@ def test_dense_matrix():
     assert X.dtype == np.float32 and X.shape == (100, 4) and X.flags.c_contiguous
     assert np.array_equal(X, wl.dense_matrix(100, 4, "uniform", seed=0))
     assert abs(wl.dense_matrix(20000, 2, "normal", seed=0).std() - 1) < 0.02
+
+
+def test_transposed_csr_is_the_transpose():
+    """The arrays the backward product uses: compared with scipy's transpose on an unsorted matrix with duplicates."""
+    import scipy.sparse as sp
+    from paper_2106_16064_amd.autograd import transpose_csr
+    rng = np.random.default_rng(5)
+    M, K, nnz = 70, 45, 600
+    rows = np.sort(rng.integers(0, M, size=nnz))
+    cols = rng.integers(0, K, size=nnz).astype(np.int32)
+    vals = rng.standard_normal(nnz).astype(np.float32)
+    rowptr = np.zeros(M + 1, dtype=np.int32)
+    np.cumsum(np.bincount(rows, minlength=M), out=rowptr[1:])
+    A = wl.CsrMatrix(M, K, rowptr, cols, vals, "t", {})
+    T = transpose_csr(A)
+    assert (T.M, T.K, T.nnz) == (K, M, nnz)
+    assert T.rowptr[0] == 0 and np.all(np.diff(T.rowptr) >= 0) and T.rowptr[-1] == nnz
+    want = sp.csr_matrix((vals.astype(np.float64), cols, rowptr), shape=(M, K)).T.toarray()
+    got = sp.csr_matrix((T.vals.astype(np.float64), T.colidx, T.rowptr), shape=(K, M)).toarray()
+    assert np.array_equal(got, want)
+    for i in range(T.M):                                   # columns ascending inside every row of A^T
+        assert np.all(np.diff(T.colidx[T.rowptr[i]:T.rowptr[i + 1]]) >= 0)
