@@ -576,3 +576,38 @@ def test_gradient_with_respect_to_the_dense_operand(dg, N):
         gref1, gbnd1 = oracle.spmm_ref(T.M, T.K, 1, T.rowptr, T.colidx, T.vals, np.ones((A.M, 1), dtype=np.float32))
         ok, worst = oracle.within_bound(v.grad.cpu().numpy().reshape(-1, 1), gref1, gbnd1, TOL)
         assert ok, worst
+
+
+def test_concurrent_calls_from_several_host_threads_and_streams(dg):
+    """The library keeps no per-call state: four host threads, each with its own stream, matrix and
+    kernel, run at the same time (ctypes releases the interpreter lock during a call) and every
+    result equals the oracle's."""
+    import threading
+    import torch
+    jobs = []
+    for i, (algo, N) in enumerate([(0, 8), (1, 2), (2, 32), (3, 1)]):
+        A = wl.sweep_csr(6000 + 500 * i, 16, "lognormal", seed=20 + i)
+        X = wl.dense_matrix(A.K, N, "uniform", seed=30 + i)
+        jobs.append(dict(A=A, X=X, algo=algo, dA=dg.DeviceCsr(A), dX=torch.from_numpy(X).cuda(),
+                         dY=torch.full((A.M, N), float("nan"), device="cuda:0"), stream=torch.cuda.Stream(), err=None))
+    torch.cuda.synchronize()
+
+    def work(job):
+        try:
+            for _ in range(20):
+                job["dA"].spmm(job["dX"], algo=job["algo"], Y=job["dY"], stream=job["stream"])
+            job["stream"].synchronize()
+        except Exception as e:          # surfaced in the main thread below
+            job["err"] = e
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for j in jobs:
+        assert j["err"] is None, j["err"]
+        A, X = j["A"], j["X"]
+        yref, bnd = oracle.spmm_ref(A.M, A.K, X.shape[1], A.rowptr, A.colidx, A.vals, X)
+        ok, worst = oracle.within_bound(j["dY"].cpu().numpy(), yref, bnd, TOL)
+        assert ok, f"algo {j['algo']}: worst |err|/bound = {worst:.3e}"
