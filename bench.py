@@ -491,7 +491,7 @@ def run_ablation(args):
 
 
 THRESHOLD_NAMES = ("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min", "pr_nnz_max",
-                   "short_avg_row_max", "short_max_row_max")
+                   "short_avg_row_max", "short_max_row_max", "wide_parallel_n")
 
 
 def run_fit(args):
@@ -508,12 +508,14 @@ def run_fit(args):
     inf = float("inf")
 
     def choose(r, t):
-        npm, pr_avg, pr_cv, sr_cv, sr_std, nnz_max, sh_avg, sh_max = t
+        npm, pr_avg, pr_cv, sr_cv, sr_std, nnz_max, sh_avg, sh_max, wide = t
+        if r["avg_row"] <= sh_avg and r["max_row"] <= sh_max:
+            return "rs_sr"
         if r["N"] <= npm:
-            if r["avg_row"] <= sh_avg and r["max_row"] <= sh_max:
-                return "rs_sr"
             return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv and r["nnz"] < nnz_max) else "nb_pr"
-        return "nb_sr" if (r["cv_row"] > sr_cv and r["stdv"] > sr_std) else "rs_sr"
+        if not (r["cv_row"] > sr_cv and r["stdv"] > sr_std):
+            return "rs_sr"
+        return "nb_pr" if r["N"] == wide else "nb_sr"
 
     def loss(rs, t):
         if not rs:
@@ -529,10 +531,10 @@ def run_fit(args):
     tree = [(npm, a, c, sc, ss) for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
             for c in (0.05, 0.1, 0.2, 0.3, 0.5, 1.0, 2.0, 4.0, 1e30) for sc in (0.3, 0.8, 1.0, 1.5, 2.0, 3.5, 1e9)
             for ss in (0, 3, 10, 30, 60)]
-    off = (inf, 0.0, 0)
+    off = (inf, 0.0, 0, 0)
     ranked = sorted(tree, key=lambda t: loss(train, t + off)[0])
-    added = [(nm, a, m) for nm in (5e6, 1e7, 2e7, 4e7, inf) for (a, m) in
-             [(0.0, 0)] + [(a, m) for a in (5, 10, 20, 40) for m in (16, 32, 64, 128, 512)]]
+    added = [(nm, a, m, w) for nm in (5e6, 1e7, 2e7, 4e7, inf) for (a, m) in
+             [(0.0, 0)] + [(a, m) for a in (5, 10, 20, 40) for m in (16, 32, 64, 128, 512)] for w in (0, 8)]
     best = min((t + x for t in ranked[:20] for x in added), key=lambda t: loss(train, t)[0])
     paper = min((t + off for t in tree if t[0] == 4 and t[2] == 1e30 and t[4] == 0), key=lambda t: loss(fit, t)[0])
     single = {k: (sum(r["ms"][k] / min(r["ms"].values()) - 1 for r in rows) / len(rows)) for k in rows[0]["ms"]}
@@ -554,7 +556,9 @@ def run_fit(args):
         "mean_loss_size_cells": loss(big, best)[0], "max_loss_size_cells": loss(big, best)[1],
         "added_rules_off": {"no_short_row_rule": variant(short_avg_row_max=0.0, short_max_row_max=0),
                             "no_size_guard": variant(pr_nnz_max=inf),
-                            "neither": variant(short_avg_row_max=0.0, short_max_row_max=0, pr_nnz_max=inf)},
+                            "no_eight_column_rule": variant(wide_parallel_n=0),
+                            "none": variant(short_avg_row_max=0.0, short_max_row_max=0, pr_nnz_max=inf,
+                                            wide_parallel_n=0)},
         "paper_shaped_tree": {"thresholds": dict(zip(THRESHOLD_NAMES, paper)), "mean_loss_fit": loss(fit, paper)[0],
                               "mean_loss_heldout": loss(test, paper)[0], "mean_loss_size_cells": loss(big, paper)[0]},
         "always_one_kernel_mean_loss": single,

@@ -88,13 +88,18 @@ typedef struct {
  *              condition is an addition: with short rows even a large cv_row
  *              leaves no row long enough to stall a wave; set sr_stdv_min to 0
  *              for the paper's rule verbatim)
- *   short rows (an addition, checked first): N <= n_parallel_max AND
- *              avg_row <= short_avg_row_max AND max_row <= short_max_row_max
- *              -> row-split sequential.  At these widths that kernel gives every
- *              row one lane; when all rows are short the whole wave is busy for
- *              max_row steps with no cross-lane step, which beat both parallel
- *              kernels on every such matrix measured.  Set short_avg_row_max
- *              to 0 to switch it off.                                          */
+ *   eight columns (an addition): N == wide_parallel_n AND the sequential side
+ *              would balance -> nnz-balanced PARALLEL kernel.  That kernel reads
+ *              eight dense columns per lane with two dwordx4 accesses, so N = 8
+ *              is still one pass over the sparse matrix, and it beat the
+ *              balanced sequential kernel by 6-18 % there.  The adaptive calls
+ *              apply it only if X and Y allow 16-byte accesses.  0 switches it off.
+ *   short rows (an addition, checked first, at every N): avg_row <=
+ *              short_avg_row_max AND max_row <= short_max_row_max -> row-split
+ *              sequential.  When no row is long, one lane group per row keeps the
+ *              whole wave busy for max_row steps with no cross-lane step and no
+ *              long-row tail; it beat the other three kernels on every such
+ *              matrix measured.  Set short_avg_row_max to 0 to switch it off.  */
 typedef struct {
     int64_t n_parallel_max;
     double pr_avg_row_min;
@@ -104,6 +109,7 @@ typedef struct {
     int64_t pr_nnz_max;
     double short_avg_row_max;
     int64_t short_max_row_max;
+    int64_t wide_parallel_n;
 } dgsp_thresholds_t;
 
 /*

@@ -45,7 +45,8 @@ class Thresholds(ctypes.Structure):
     _fields_ = [("n_parallel_max", ctypes.c_int64), ("pr_avg_row_min", ctypes.c_double),
                 ("pr_cv_max", ctypes.c_double), ("sr_cv_min", ctypes.c_double),
                 ("sr_stdv_min", ctypes.c_double), ("pr_nnz_max", ctypes.c_int64),
-                ("short_avg_row_max", ctypes.c_double), ("short_max_row_max", ctypes.c_int64)]
+                ("short_avg_row_max", ctypes.c_double), ("short_max_row_max", ctypes.c_int64),
+                ("wide_parallel_n", ctypes.c_int64)]
 
 
 class DgspError(RuntimeError):

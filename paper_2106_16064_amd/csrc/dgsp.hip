@@ -251,6 +251,9 @@ int launch_nb_pr_v(const Problem& p) {
 }
 
 int launch_nb_pr(const Problem& p) {
+    // eight dense columns per lane (two dwordx4 accesses) when N allows: one pass over A instead of two
+    if (vector_width(p) == 4 && p.N % 8 == 0 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
+        return launch_nb_pr_v<8, 1>(p);
     switch (vector_width(p)) {
         case 4: return launch_nb_pr_v<4, 1>(p);
         case 2: return launch_nb_pr_v<2, 2>(p);
@@ -300,6 +303,7 @@ dgsp_thresholds_t g_thresholds = {
     /* pr_nnz_max      */ 5000000,
     /* short_avg_row_max */ 20.0,
     /* short_max_row_max */ 64,
+    /* wide_parallel_n   */ 8,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
@@ -358,7 +362,12 @@ extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, co
                                 int64_t ldy, int algo, const dgsp_features_t* features, void* stream) {
     if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
     if (features && nnz < 0) nnz = features->nnz;
-    if (algo == DGSP_AUTO && features && N >= 1) algo = dgsp_select_algo(features, N);
+    if (algo == DGSP_AUTO && features && N >= 1) {
+        algo = dgsp_select_algo(features, N);
+        if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max &&
+            (widest_vector(N, X, Y) < 4 || ldx % 4 != 0 || ldy % 4 != 0))
+            algo = DGSP_NB_SR;        // the eight-column rule needs 16-byte accesses
+    }
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                features ? features->col_span : 0.0, 0, ldx, ldy);
 }
@@ -381,6 +390,7 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
     if (features->M != M || features->nnz < 0) return DGSP_ERR_INVALID_ARG;
     int algo = (N >= 1) ? dgsp_select_algo(features, N) : DGSP_NB_PR;
     if (algo < 0) return DGSP_ERR_INVALID_ARG;
+    if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max && widest_vector(N, X, Y) < 4) algo = DGSP_NB_SR;
     if (chosen) *chosen = algo;
     return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, features->col_span);
 }
@@ -389,15 +399,17 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
 extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     if (!f || N < 1) return DGSP_AUTO;
     const dgsp_thresholds_t& t = g_thresholds;
+    // all rows short: one lane group per row keeps a wave busy with no cross-lane step and no idle tail
+    if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
     if (N <= t.n_parallel_max) {
-        // all rows short: one lane per row keeps a wave busy with no cross-lane step at all
-        if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
         // parallel reduction: long rows keep a row's lanes busy, short rows idle them
         const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max && f->nnz < t.pr_nnz_max;
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;
     }
     // sequential reduction: balance only when stdv_row / avg_row says rows are uneven
-    return (f->cv_row > t.sr_cv_min && f->stdv_row > t.sr_stdv_min) ? DGSP_NB_SR : DGSP_RS_SR;
+    if (!(f->cv_row > t.sr_cv_min && f->stdv_row > t.sr_stdv_min)) return DGSP_RS_SR;
+    // eight columns fit one lane of the balanced parallel kernel: still a single pass
+    return (t.wide_parallel_n > 0 && N == t.wide_parallel_n) ? DGSP_NB_PR : DGSP_NB_SR;
 }
 
 extern "C" void dgsp_get_thresholds(dgsp_thresholds_t* out) {

@@ -59,7 +59,11 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
 
 template <int V>
 __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&x)[V]) {
-    if constexpr (V == 4) {
+    if constexpr (V == 8) {                                  // two dwordx4 accesses
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        const float4 u = *reinterpret_cast<const float4*>(p + 4);
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; x[4] = u.x; x[5] = u.y; x[6] = u.z; x[7] = u.w;
+    } else if constexpr (V == 4) {
         const float4 t = *reinterpret_cast<const float4*>(p);
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
     } else if constexpr (V == 2) {
@@ -72,7 +76,10 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&x)
 
 template <int V>
 __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x)[V]) {
-    if constexpr (V == 4) {
+    if constexpr (V == 8) {
+        *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+    } else if constexpr (V == 4) {
         *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
     } else if constexpr (V == 2) {
         *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
@@ -122,7 +129,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, uns
 // cause no memory traffic.  `aux` 2 marks the load non-temporal.
 template <int V>
 __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V]) {
-    if constexpr (V == 4) {
+    if constexpr (V == 8) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        // the second half of a switched-off lane stays out of range: 0xffffffff + 16 would wrap into it
+        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 16u;
+        const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
+        const f4 u = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, second, 0, 0));
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; x[4] = u.x; x[5] = u.y; x[6] = u.z; x[7] = u.w;
+    } else if constexpr (V == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
         const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
@@ -139,7 +153,15 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
 
 template <int V>
 __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
-    if constexpr (V == 4) {
+    if constexpr (V == 8) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 16u;
+        const f4 t = {x[0], x[1], x[2], x[3]};
+        const f4 u = {x[4], x[5], x[6], x[7]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, u), rsrc, second, 0, 0);
+    } else if constexpr (V == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
         const f4 t = {x[0], x[1], x[2], x[3]};

@@ -73,7 +73,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0)      # the paper's rule verbatim (no added guards)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0, 0)      # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -105,10 +105,17 @@ def test_selection_rules_follow_the_decision_tree():
         dg.dgsp_set_thresholds(t)
         f = feat(4, 0.5); f.max_row = 16
         assert dg.dgsp_select_algo(f, 2) == dg.RS_SR                       # every row short: one lane per row
+        assert dg.dgsp_select_algo(f, 64) == dg.RS_SR                      # ... at every width
         f.max_row = 400
         assert dg.dgsp_select_algo(f, 2) != dg.RS_SR                       # one long row: back to the tree
         f = feat(40, 0.1); f.max_row = 50
         assert dg.dgsp_select_algo(f, 2) != dg.RS_SR                       # rows not short on average
+        t.wide_parallel_n, t.n_parallel_max = 8, 4                         # the added eight-column rule
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(feat(64, 1.5), 8) == dg.NB_PR           # balanced, and 8 columns fit one lane
+        assert dg.dgsp_select_algo(feat(64, 1.5), 16) == dg.NB_SR
+        assert dg.dgsp_select_algo(feat(64, 1.5), 7) == dg.NB_SR
+        assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_SR           # even rows: row-split as before
         L = dg.lib()
         assert L.dgsp_select_algo(None, 4) == dg.AUTO
         assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
