@@ -218,7 +218,8 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
                                 long long col_blocks = 1) {
     const long long cus = device_info().cus;
     const long long cap = cus * blocks_per_cu;
-    if (p.nnz < 0) return (unsigned)cap;
+    // entry count unknown on the host (the 10-argument call): what serves large matrices best
+    if (p.nnz < 0) return (unsigned)(parallel && blocks_per_cu > 2 ? cus * 2 : cap);
     const long long tiles = (p.nnz + p.M + tile - 1) / tile;
     const long long waves = cus * kWavesPerBlock;
     if (tiles <= waves) return clamp_blocks((tiles + kWavesPerBlock - 1) / kWavesPerBlock, cap);
