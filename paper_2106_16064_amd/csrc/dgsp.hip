@@ -256,7 +256,7 @@ int launch_nb_pr(const Problem& p) {
     if (vector_width(p) == 4 && p.N % 8 == 0 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
         return launch_nb_pr_v<8, 1>(p);
     switch (vector_width(p)) {
-        case 4: return launch_nb_pr_v<4, 1>(p);
+        case 4: return launch_nb_pr_v<4, 2>(p);
         case 2: return launch_nb_pr_v<2, 2>(p);
         default: return launch_nb_pr_v<1, 2>(p);
     }
