@@ -80,7 +80,7 @@ typedef struct {
  *              nnz < pr_nnz_max -> row-split, else nnz-balanced (the last two
  *              conditions are additions: the paper's parallel-side rule looks at
  *              avg_row only.  The balanced kernel streams faster but needs a
- *              second, small launch, which pays off from a few million stored
+ *              second, small launch, which pays off from some ten million stored
  *              entries on.  Set pr_cv_max to a huge value and
  *              pr_nnz_max to INT64_MAX to get the paper's rule verbatim)
  *   sequential: cv_row > sr_cv_min AND stdv_row > sr_stdv_min -> nnz-balanced,

@@ -297,11 +297,11 @@ int launch_nb_sr(const Problem& p) {
 // banded and random matrices (the paper prints no threshold values, Section 2.2).
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
-    /* pr_avg_row_min  */ 0.0,
+    /* pr_avg_row_min  */ 48.0,
     /* pr_cv_max       */ 0.05,
     /* sr_cv_min       */ 0.3,
     /* sr_stdv_min     */ 3.0,
-    /* pr_nnz_max      */ 5000000,
+    /* pr_nnz_max      */ 20000000,
     /* short_avg_row_max */ 20.0,
     /* short_max_row_max */ 64,
     /* wide_parallel_n   */ 8,
