@@ -611,3 +611,48 @@ def test_concurrent_calls_from_several_host_threads_and_streams(dg):
         yref, bnd = oracle.spmm_ref(A.M, A.K, X.shape[1], A.rowptr, A.colidx, A.vals, X)
         ok, worst = oracle.within_bound(j["dY"].cpu().numpy(), yref, bnd, TOL)
         assert ok, f"algo {j['algo']}: worst |err|/bound = {worst:.3e}"
+
+
+# ------------------------------------------------------------------ more shapes at the edges
+@pytest.mark.parametrize("N", [1000, 1024, 4096])
+def test_very_wide_dense_operands(dg, N):
+    """Widths far beyond a wave's 64 x 4 columns: several column blocks per row (grid.y)."""
+    A = wl.sweep_csr(300, 6, "lognormal", seed=N)
+    check(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=1))
+
+
+def test_single_column_matrix_and_single_row_matrix(dg):
+    """K = 1 (every entry gathers the same row of X) and M = 1 (one row holds everything)."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 2, size=5000)
+    A = wl.CsrMatrix(5000, 1, np.concatenate([[0], np.cumsum(lens)]).astype(np.int32),
+                     np.zeros(int(lens.sum()), dtype=np.int32), rng.standard_normal(int(lens.sum())).astype(np.float32),
+                     "one_column", {})
+    for N in (1, 4, 33):
+        check(dg, A, wl.dense_matrix(1, N, "normal", seed=N))
+    cols = np.sort(rng.choice(20000, size=7000, replace=False)).astype(np.int32)
+    B = wl.CsrMatrix(1, 20000, np.array([0, 7000], dtype=np.int32), cols,
+                     rng.standard_normal(7000).astype(np.float32), "one_row", {})
+    for N in (1, 2, 8, 64):
+        check(dg, B, wl.dense_matrix(20000, N, "uniform", seed=N))
+
+
+def test_rows_in_views_far_apart(dg):
+    """A leading dimension much larger than the width: rows of X and Y 4096 floats apart."""
+    import torch
+    A = wl.poisson_csr(700, 600, 7.0, seed=8)
+    N, ld = 8, 4096
+    rng = np.random.default_rng(9)
+    Xw = rng.standard_normal((A.K, ld)).astype(np.float32)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, np.ascontiguousarray(Xw[:, 100:100 + N]))
+    dA = dg.DeviceCsr(A)
+    dXw = torch.from_numpy(Xw).cuda()
+    for algo in (0, 1, 2, 3):
+        dYw = torch.full((A.M, ld), float("nan"), dtype=torch.float32, device="cuda:0")
+        dg.dgsp_spmm_csr_ld(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dXw[:, 100:100 + N], dYw[:, 2000:2000 + N],
+                            algo, dA.features)
+        torch.cuda.synchronize()
+        Yw = dYw.cpu().numpy()
+        ok, worst = oracle.within_bound(Yw[:, 2000:2000 + N], yref, bnd, TOL)
+        assert ok, (algo, worst)
+        assert np.isnan(Yw[:, :2000]).all() and np.isnan(Yw[:, 2000 + N:]).all()
