@@ -262,6 +262,22 @@ int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz,
                      const dgsp_features_t *features, void *stream);
 
 /*
+ * The scaled form  Y = alpha * (A X) + beta * Y  on strided views (the paper
+ * computes Y = A X; this is the usual BLAS-style generalisation, computed by
+ * variants of the same four kernels that scale a row's sum as they write it).
+ * With beta == 0 the old contents of Y are not read (they may be anything,
+ * NaN included).  Rows of A without entries give beta * Y.  Rows whose partial
+ * sums meet through atomic adds are first multiplied by beta by the prepare
+ * launch.  Available for X below 4 GB, else DGSP_ERR_UNSUPPORTED.  Other
+ * arguments, vector-width rule and algo == DGSP_AUTO as in dgsp_spmm_csr_ld.
+ */
+int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                        const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *X, int64_t ldx, float *Y, int64_t ldy,
+                        float alpha, float beta, int algo,
+                        const dgsp_features_t *features, void *stream);
+
+/*
  * Measurement aid: the same multiplication with one of the paper's optimisations
  * switched off, for the comparisons of Sections 2.1.2 and 2.1.3.  Same arguments,
  * layouts, result and error behaviour as dgsp_spmm_csr_nnz; `switches` is a

@@ -23,7 +23,7 @@ EXPORTS = (
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
     "dgsp_spmm_csr_ablation", "dgsp_features_from_csr_device", "dgsp_autotune",
-    "dgsp_spmm_csr_ld",
+    "dgsp_spmm_csr_ld", "dgsp_spmm_csr_axpby",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING = 1, 2
@@ -92,6 +92,9 @@ def lib():
                                     ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci), vp]
         L.dgsp_spmm_csr_ld.restype = ci
         L.dgsp_spmm_csr_ld.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, ci, ctypes.POINTER(Features), vp]
+        L.dgsp_spmm_csr_axpby.restype = ci
+        L.dgsp_spmm_csr_axpby.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, ctypes.c_float, ctypes.c_float,
+                                          ci, ctypes.POINTER(Features), vp]
         L.dgsp_spmm_csr_ablation.restype = ci
         L.dgsp_spmm_csr_ablation.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
         L.dgsp_gather_probe.restype = ci
@@ -178,6 +181,23 @@ def dgsp_spmm_csr_ld(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo=AUTO, featur
                                 _ptr(Y), int(ldy), int(algo),
                                 ctypes.byref(features) if features is not None else None, _stream(stream))
     _check(rc, "dgsp_spmm_csr_ld")
+
+
+def dgsp_spmm_csr_axpby(M, K, N, nnz, rowptr, colidx, vals, X, Y, alpha=1.0, beta=0.0, algo=AUTO, features=None,
+                        stream=None):
+    """``Y = alpha * A X + beta * Y`` on 2-D views (rows ``stride(0)`` floats apart, unit column stride)."""
+    import torch
+    for name, t in (("X", X), ("Y", Y)):
+        if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise DgspError(f"{name} must be a 2-D float32 GPU view with unit column stride")
+    if X.shape != (K, N) or Y.shape != (M, N):
+        raise DgspError("X must be K x N and Y M x N")
+    ldx = X.stride(0) if K > 1 else max(N, X.stride(0))
+    ldy = Y.stride(0) if M > 1 else max(N, Y.stride(0))
+    rc = lib().dgsp_spmm_csr_axpby(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), int(ldx),
+                                   _ptr(Y), int(ldy), float(alpha), float(beta), int(algo),
+                                   ctypes.byref(features) if features is not None else None, _stream(stream))
+    _check(rc, "dgsp_spmm_csr_axpby")
 
 
 def dgsp_spmm_csr_ablation(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, switches, features=None, stream=None):

@@ -70,6 +70,8 @@ struct Problem {
     int phase = DGSP_PHASE_ALL;
     double col_span = 0.0;   // mean column span of a row / K; 0 = unknown
     int switches = 0;        // DGSP_ABL_* (measurement aids)
+    bool scaled = false;     // Y = alpha * A X + beta * Y instead of Y = A X
+    float alpha = 1.0f, beta = 0.0f;
 };
 
 inline int vector_width(const Problem& p) {
@@ -120,6 +122,15 @@ int launch_rs_pr_v(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));
+    if (p.scaled) {
+        if constexpr (XBUF) {
+            DGSP_LAUNCH((rs_pr_kernel<V, true, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
+                        p.Y, logG, Scaling{p.alpha, p.beta});
+            return DGSP_OK;
+        } else {
+            return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
+        }
+    }
     DGSP_LAUNCH((rs_pr_kernel<V, XBUF>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
@@ -155,6 +166,15 @@ int launch_rs_sr_v(const Problem& p) {
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
+    if (p.scaled) {
+        if constexpr (XBUF) {
+            DGSP_LAUNCH((rs_sr_kernel<V, true, DEPTH, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals,
+                        p.X, p.Y, logG, Scaling{p.alpha, p.beta});
+            return DGSP_OK;
+        } else {
+            return DGSP_ERR_UNSUPPORTED;
+        }
+    }
     DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
 }
@@ -199,7 +219,8 @@ int launch_rs_sr(const Problem& p) {
 // (tile_log2 < 0: not cut further).
 int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum_log2, int tile_log2) {
     const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.ldy, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2);
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.ldy, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2,
+                p.scaled ? p.beta : 0.0f);
     return DGSP_OK;
 }
 
@@ -246,8 +267,13 @@ int launch_nb_pr_v(const Problem& p) {
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
-    if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+    if (p.phase != DGSP_PHASE_PREPARE) {
+        if (p.scaled)
+            DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
+                        Scaling{p.alpha, p.beta});
+        else
+            DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+    }
     return DGSP_OK;
 }
 
@@ -271,11 +297,20 @@ int launch_nb_sr_v(const Problem& p) {
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
     if (p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
+    if (p.scaled && !XBUF) return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
-    if (p.phase != DGSP_PHASE_PREPARE)
-        DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    if (p.phase != DGSP_PHASE_PREPARE) {
+        if (p.scaled) {
+            if constexpr (XBUF)
+                DGSP_LAUNCH((nb_sr_kernel<V, true, DEPTH, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
+                            p.vals, p.X, p.Y, logG, Scaling{p.alpha, p.beta});
+        } else {
+            DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
+                        logG);
+        }
+    }
     return DGSP_OK;
 }
 
@@ -309,7 +344,7 @@ dgsp_thresholds_t g_thresholds = {
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
         const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
-        double col_span = 0.0, int switches = 0, int64_t ldx = -1, int64_t ldy = -1) {
+        double col_span = 0.0, int switches = 0, int64_t ldx = -1, int64_t ldy = -1, const Scaling* scaling = nullptr) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
     if (ldx < 0) ldx = N;            // packed rows unless the caller says otherwise
     if (ldy < 0) ldy = N;
@@ -325,6 +360,7 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
     Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span, switches};
+    if (scaling) { p.scaled = true; p.alpha = scaling->alpha; p.beta = scaling->beta; }
     switch (algo) {
         case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
         case DGSP_RS_PR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_pr(p);
@@ -371,6 +407,23 @@ extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, co
     }
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                features ? features->col_span : 0.0, 0, ldx, ldy);
+}
+
+extern "C" int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                   const int32_t* colidx, const float* vals, const float* X, int64_t ldx, float* Y,
+                                   int64_t ldy, float alpha, float beta, int algo, const dgsp_features_t* features,
+                                   void* stream) {
+    if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
+    if (features && nnz < 0) nnz = features->nnz;
+    if (algo == DGSP_AUTO && features && N >= 1) {
+        algo = dgsp_select_algo(features, N);
+        if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max &&
+            (widest_vector(N, X, Y) < 4 || ldx % 4 != 0 || ldy % 4 != 0))
+            algo = DGSP_NB_SR;
+    }
+    const Scaling sc{alpha, beta};
+    return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
+               features ? features->col_span : 0.0, 0, ldx, ldy, &sc);
 }
 
 extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,

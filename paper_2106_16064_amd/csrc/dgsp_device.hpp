@@ -176,6 +176,35 @@ __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, un
     }
 }
 
+// Scaling of a finished result (the kernels' AXPBY variants): v = alpha * v + beta * old.  With
+// beta == 0 the old value is not read, so the output buffer may hold anything beforehand.
+struct Scaling { float alpha, beta; };
+template <int V>
+__device__ __forceinline__ void scale_into(float (&v)[V], const float* __restrict__ old, Scaling s) {
+    if (s.beta != 0.0f) {
+        float o[V];
+        load_vec<V>(old, o);
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = fmaf(s.alpha, v[i], s.beta * o[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] *= s.alpha;
+    }
+}
+// the same with the old value behind a buffer descriptor (a switched-off lane reads zeros)
+template <int V>
+__device__ __forceinline__ void scale_into(float (&v)[V], __amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, Scaling s) {
+    if (s.beta != 0.0f) {                           // wave-uniform
+        float o[V];
+        buffer_load_vec<V>(rsrc, byte_offset, o);
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = fmaf(s.alpha, v[i], s.beta * o[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] *= s.alpha;
+    }
+}
+
 // Column index / value streams: non-temporal dword loads through a descriptor.
 __device__ __forceinline__ int buffer_stream_i32(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
     return (int)__builtin_amdgcn_raw_buffer_load_b32(r, byte_offset, 0, 2);

@@ -41,12 +41,12 @@ __host__ __device__ __forceinline__ int pr_lanes_log2(long long nnz, long long M
 
 constexpr int kRsPrUnroll = 4;   // row groups a wave keeps in flight
 
-template <int V, bool XBUF>
+template <int V, bool XBUF, bool AXPBY = false>
 __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG_in) {
+                                                        int logG_in, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int U = kRsPrUnroll;
     const int lane = lane_id();
     const unsigned nnz = (unsigned)rowptr[M];
@@ -133,7 +133,11 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
             for (int u = 0; u < U; ++u) {
                 segmented_scan<V>(acc[u], gl, lane, G);   // all 64 lanes arrive here together
                 const unsigned long long row = row0 + (unsigned)(u * rows_per_wave + g);
-                if (row < (unsigned long long)M && gl == G - 1) store_vec<V>(Y + (size_t)row * ldy + n0, acc[u]);
+                if (row < (unsigned long long)M && gl == G - 1) {
+                    float* y = Y + (size_t)row * ldy + n0;
+                    if constexpr (AXPBY) scale_into<V>(acc[u], y, sc);
+                    store_vec<V>(y, acc[u]);
+                }
             }
         }
     }
@@ -163,12 +167,12 @@ constexpr int kRsSrTile = 512;   // cached pairs per wave and round
 // at depth 4).  Rows that hit in cache anyway want the latency hidden instead (27-point stencil,
 // N = 8: 204 us at depth 4, 260 us at depth 1), and so do rows of uneven length.  The host picks.
 
-template <int V, bool XBUF, int DEPTH>
+template <int V, bool XBUF, int DEPTH, bool AXPBY = false>
 __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG) {
+                                                        int logG, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int T = kRsSrTile;
     __shared__ int s_col[kWavesPerBlock][T];
     __shared__ float s_val[kWavesPerBlock][T];
@@ -247,7 +251,11 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
                 }
             }
         }
-        if (live && col_ok) store_vec<V>(Y + (size_t)row * ldy + n, acc);
+        if (live && col_ok) {
+            float* y = Y + (size_t)row * ldy + n;
+            if constexpr (AXPBY) scale_into<V>(acc, y, sc);
+            store_vec<V>(y, acc);
+        }
     }
 }
 
@@ -350,7 +358,8 @@ struct EvenSplit {
     }
 };
 
-// Zeroes the rows whose items do not all lie in one piece of the partition.
+// Zeroes the rows whose items do not all lie in one piece of the partition (beta != 0, the scaled
+// variants: multiplies them by beta instead, so that the partial sums added later land on beta * Y).
 // unit > 0: pieces are the multiples of `unit` items.  unit == 0: pieces are
 // the `parts` chunks of the even split with quanta of 2^quantum_log2 items, cut
 // further into tiles of 2^tile_log2 items counted from the chunk's start when
@@ -359,7 +368,7 @@ struct EvenSplit {
 // a wave then clears its split rows together, 64 columns per store.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ldy, const int* __restrict__ rowptr,
                                                              float* __restrict__ Y, unsigned unit, unsigned parts,
-                                                             unsigned quantum_log2, int tile_log2) {
+                                                             unsigned quantum_log2, int tile_log2, float beta) {
     const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
     bool split = false;
     if (row < M) {
@@ -382,7 +391,7 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ld
     if (N <= 8) {                                      // narrow rows: the thread clears its own
         if (split) {
             float* y = Y + (size_t)row * ldy;
-            for (int n = 0; n < N; ++n) y[n] = 0.0f;
+            for (int n = 0; n < N; ++n) y[n] = beta != 0.0f ? beta * y[n] : 0.0f;
         }
         return;
     }
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ld
         const int src = __ffsll((long long)todo) - 1;
         todo &= todo - 1;
         float* y = Y + (size_t)(row0 + src) * ldy;
-        for (int n = lane; n < N; n += kWave) y[n] = 0.0f;
+        for (int n = lane; n < N; n += kWave) y[n] = beta != 0.0f ? beta * y[n] : 0.0f;
     }
 }
 
@@ -482,11 +491,12 @@ constexpr unsigned kNoRow = 0xffffffffu;
 // the next tile's loads stay in flight while this tile is reduced.
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
-template <int V, int KQ>
+template <int V, int KQ, bool AXPBY = false>
 __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
-                                                        const float* __restrict__ X, float* __restrict__ Y) {
+                                                        const float* __restrict__ X, float* __restrict__ Y,
+                                                        Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int E = 4 * KQ;
     constexpr int W = kWave * E;
     __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the tile's first entry
@@ -510,7 +520,14 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         float zero[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) zero[i] = 0.0f;
-        for (unsigned r = d0 + lane; r < d1; r += kWave) store_vec<V>(Y + (size_t)r * ldy + n0, zero);
+        for (unsigned r = d0 + lane; r < d1; r += kWave) {
+            float* y = Y + (size_t)r * ldy + n0;
+            float out[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) out[i] = 0.0f;
+            if constexpr (AXPBY) scale_into<V>(out, y, sc);
+            store_vec<V>(y, out);
+        }
         continue;
     }
 
@@ -697,7 +714,16 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
                 load_vec<V>(buf + (size_t)t * V, val);
                 const bool live = t < nrows;
                 const bool shared = first_split && is + t == r_first;   // finished by an atomic add instead
-                buffer_store_vec<V>(yrows, (live && !shared) ? (unsigned)t * (unsigned)ldy * 4u : kOutOfRange, val);
+                const unsigned off = (live && !shared) ? (unsigned)t * (unsigned)ldy * 4u : kOutOfRange;
+                if constexpr (AXPBY) {
+                    if (live && shared) {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) val[i] *= sc.alpha;          // lands on beta * Y (prepare)
+                    } else {
+                        scale_into<V>(val, yrows, off, sc);
+                    }
+                }
+                buffer_store_vec<V>(yrows, off, val);
                 if (live && shared) atomic_add_vec<V>(Y + (size_t)(is + t) * ldy + n0, val);
             };
             write_rows(0);
@@ -718,6 +744,10 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     bool any = false;
 #pragma unroll
     for (int i = 0; i < V; ++i) any |= carry[i] != 0.0f;
+    if constexpr (AXPBY) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) carry[i] *= sc.alpha;
+    }
     if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * ldy + n0, carry);
     }   // next chunk
 }
@@ -744,12 +774,12 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 constexpr int kNbSrTile = 512;
 constexpr int kNbSrLogTile = 9;
 
-template <int V, bool XBUF, int DEPTH>
+template <int V, bool XBUF, int DEPTH, bool AXPBY = false>
 __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG) {
+                                                        int logG, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int W = kNbSrTile;
     constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
     __shared__ int s_col[kWavesPerBlock][W];
@@ -861,7 +891,16 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                         const int start = tz == 0 ? (int)(rs_first - js) : (int)ends[tz - 1];   // negative: began before the tile
                         empty = end == start;
                     }
-                    buffer_store_vec<V>(yrows, (empty && col_ok) ? (unsigned)tz * (unsigned)ldy * 4u + n_bytes : kOutOfRange, zero);
+                    const unsigned off = (empty && col_ok) ? (unsigned)tz * (unsigned)ldy * 4u + n_bytes : kOutOfRange;
+                    if constexpr (AXPBY) {
+                        float out[V];
+#pragma unroll
+                        for (int i = 0; i < V; ++i) out[i] = 0.0f;
+                        scale_into<V>(out, yrows, off, sc);               // beta * Y
+                        buffer_store_vec<V>(yrows, off, out);
+                    } else {
+                        buffer_store_vec<V>(yrows, off, zero);
+                    }
                 }
             }
         }
@@ -923,7 +962,16 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
         auto close_row = [&](bool closing) {
             if (__ballot(closing) != 0ull) {                 // wave-uniform
                 const bool direct = closing && cur_first >= dg;
-                buffer_store_vec<V>(yrows, direct ? (unsigned)t * (unsigned)ldy * 4u + n_bytes : kOutOfRange, acc);
+                const unsigned off = direct ? (unsigned)t * (unsigned)ldy * 4u + n_bytes : kOutOfRange;
+                if constexpr (AXPBY) {
+                    float out[V];
+#pragma unroll
+                    for (int i = 0; i < V; ++i) out[i] = acc[i];
+                    scale_into<V>(out, yrows, off, sc);
+                    buffer_store_vec<V>(yrows, off, out);
+                } else {
+                    buffer_store_vec<V>(yrows, off, acc);
+                }
                 if (closing) {
                     if (!direct) to_slot(true);
 #pragma unroll
@@ -977,7 +1025,16 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                     load_vec<V>(slot_acc + (size_t)(s * G + gl) * V, val);
                     float* y = Y + (size_t)row * ldy + n;
                     // started inside the tile (s > 0) and ended inside it: nobody else has a part of this row
-                    if (s > 0 && slot_end[s]) store_vec<V>(y, val); else atomic_add_vec<V>(y, val);
+                    const bool whole = s > 0 && slot_end[s];
+                    if constexpr (AXPBY) {
+                        if (whole) {
+                            scale_into<V>(val, y, sc);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < V; ++i) val[i] *= sc.alpha;          // lands on beta * Y (prepare)
+                        }
+                    }
+                    if (whole) store_vec<V>(y, val); else atomic_add_vec<V>(y, val);
                 }
             }
         }

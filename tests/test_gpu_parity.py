@@ -656,3 +656,62 @@ def test_rows_in_views_far_apart(dg):
         ok, worst = oracle.within_bound(Yw[:, 2000:2000 + N], yref, bnd, TOL)
         assert ok, (algo, worst)
         assert np.isnan(Yw[:, :2000]).all() and np.isnan(Yw[:, 2000 + N:]).all()
+
+
+# ------------------------------------------------------------------ the scaled form
+@pytest.mark.parametrize("N", [1, 2, 4, 8, 32, 100])
+@pytest.mark.parametrize("alpha,beta", [(1.0, 0.0), (2.5, 0.0), (1.0, 1.0), (-0.75, 0.5), (0.0, 2.0)])
+def test_scaled_form_alpha_beta(dg, N, alpha, beta):
+    """Y = alpha * A X + beta * Y0 through every kernel: compared with alpha * Yref + beta * Y0 formed in
+    fp64 from the oracle's product, bound alpha*|A||X| + |beta Y0|.  With beta = 0, Y0 is NaN on purpose."""
+    import torch
+    A = wl.rmat_csr(scale=13, avg_degree=10, seed=40 + N)          # hubs, many empty rows
+    X = wl.dense_matrix(A.K, N, "normal", seed=N)
+    Y0 = wl.dense_matrix(A.M, N, "uniform", seed=100 + N)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    want = alpha * yref + (beta * Y0.astype(np.float64) if beta != 0.0 else 0.0)
+    bound = abs(alpha) * bnd + abs(beta) * np.abs(Y0.astype(np.float64))
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    for algo in (0, 1, 2, 3, dg.AUTO):
+        print(f"[case] axpby N={N} alpha={alpha} beta={beta} algo={algo}", flush=True)
+        dY = torch.from_numpy(Y0).cuda() if beta != 0.0 else torch.full((A.M, N), float("nan"), device="cuda:0")
+        dg.dgsp_spmm_csr_axpby(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, alpha, beta, algo, dA.features)
+        torch.cuda.synchronize()
+        Y = dY.cpu().numpy()
+        assert not np.isnan(Y).any()
+        ok, worst = oracle.within_bound(Y, want, bound, 2e-5)      # one more rounding than the plain product
+        assert ok, f"algo {algo}: worst |err|/bound = {worst:.3e}"
+
+
+def test_scaled_form_on_views_and_without_entries(dg):
+    import torch
+    A = wl.sweep_csr(1500, 9, "lognormal", seed=4)
+    N, ldx, ldy = 4, 12, 8
+    rng = np.random.default_rng(2)
+    Xw = rng.standard_normal((A.K, ldx)).astype(np.float32)
+    Yw0 = rng.standard_normal((A.M, ldy)).astype(np.float32)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, np.ascontiguousarray(Xw[:, 4:8]))
+    want = 3.0 * yref - 1.0 * Yw0[:, 4:8].astype(np.float64)
+    bound = 3.0 * bnd + np.abs(Yw0[:, 4:8].astype(np.float64))
+    dA = dg.DeviceCsr(A)
+    dXw = torch.from_numpy(Xw).cuda()
+    for algo in (0, 1, 2, 3):
+        dYw = torch.from_numpy(Yw0).cuda()
+        dg.dgsp_spmm_csr_axpby(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dXw[:, 4:8], dYw[:, 4:8], 3.0, -1.0, algo,
+                               dA.features)
+        torch.cuda.synchronize()
+        Yw = dYw.cpu().numpy()
+        ok, worst = oracle.within_bound(Yw[:, 4:8], want, bound, 2e-5)
+        assert ok, (algo, worst)
+        assert np.array_equal(Yw[:, :4], Yw0[:, :4])                # the rest of Y's rows is untouched
+    # a matrix without entries: Y = beta * Y
+    E = wl.csr_from_lens(np.zeros(300, dtype=np.int64), 50, seed=0, name="empty")
+    dE = dg.DeviceCsr(E)
+    for algo in (0, 1, 2, 3):
+        Y0 = rng.standard_normal((300, 2)).astype(np.float32)
+        dY = torch.from_numpy(Y0).cuda()
+        dg.dgsp_spmm_csr_axpby(300, 50, 2, 0, dE.rowptr, dE.colidx, dE.vals, torch.zeros((50, 2), device="cuda:0"), dY,
+                               7.0, 0.5, algo, dE.features)
+        torch.cuda.synchronize()
+        assert np.array_equal(dY.cpu().numpy(), (np.float32(0.5) * Y0))
