@@ -47,6 +47,23 @@ def build(verbose: bool = True, extra_flags=()) -> Path:
     return LIB
 
 
+EXAMPLE_SRC = CSRC / "c_abi_example.c"
+EXAMPLE = HERE / "c_abi_example"
+
+
+def build_c_example(verbose: bool = True) -> Path:
+    """A plain-C caller of the library (gcc, no C++): shows and tests the C-ABI from outside Python."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include", "-o", str(EXAMPLE), str(EXAMPLE_SRC),
+           f"-L{HERE}", "-ldgsp", f"-L{rocm}/lib", "-lamdhip64", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{rocm}/lib", "-lm"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"gcc failed on the C example:\n{res.stderr}")
+    return EXAMPLE
+
+
 def is_stale() -> bool:
     if not LIB.exists():
         return True
@@ -56,3 +73,4 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     build()
+    build_c_example()

@@ -715,3 +715,15 @@ def test_scaled_form_on_views_and_without_entries(dg):
                                7.0, 0.5, algo, dE.features)
         torch.cuda.synchronize()
         assert np.array_equal(dY.cpu().numpy(), (np.float32(0.5) * Y0))
+
+
+def test_plain_c_caller_of_the_library():
+    """The C-ABI from a C program (built by the package's build step): all four kernels and the
+    adaptive call against a host loop; the program's exit code says whether every result was in bound."""
+    import subprocess
+    from paper_2106_16064_amd import build
+    assert build.EXAMPLE.exists(), "run `python -m paper_2106_16064_amd.build` first"
+    res = subprocess.run([str(build.EXAMPLE)], capture_output=True, text=True, timeout=120)
+    print(res.stdout)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.count(" ok") == 5

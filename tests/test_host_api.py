@@ -151,3 +151,10 @@ def test_column_span_feature():
     f3 = dg.dgsp_features_from_csr_host(3, 10, np.array([0, 2, 2, 3], np.int32), np.array([1, 3, 5], np.int32))
     assert f3.col_span == pytest.approx(0.2)
     assert dg.dgsp_features_from_rowptr_host(3, 10, np.array([0, 2, 2, 3], np.int32)).col_span == 0.0
+
+
+def test_c_example_builds_and_links_against_the_library():
+    """The plain-C caller compiles with gcc against include/dgsp.h and links to libdgsp.so (running it needs a GPU)."""
+    from paper_2106_16064_amd import build
+    exe = build.build_c_example(verbose=False)
+    assert exe.exists() and exe.stat().st_size > 0
