@@ -214,12 +214,11 @@ int launch_rs_sr(const Problem& p) {
 }
 
 // ---------------------------------------------------------------- balanced launches
-// Zeroes the rows split by a multiple of `unit` merge-path items; unit == 0: by the `parts` chunks
-// the main kernel derives (quanta of 2^quantum_log2 items), cut into tiles of 2^tile_log2 items
-// (tile_log2 < 0: not cut further).
-int launch_prepare(const Problem& p, unsigned unit, unsigned parts, unsigned quantum_log2, int tile_log2) {
+// Zeroes (scaled form: multiplies by beta) the rows split by the `parts` chunks the main kernel derives
+// (quanta of 2^quantum_log2 items), cut into tiles of 2^tile_log2 items (tile_log2 < 0: not cut further).
+int launch_prepare(const Problem& p, unsigned parts, unsigned quantum_log2, int tile_log2) {
     const dim3 grid((unsigned)(((long long)p.M + kBlock - 1) / kBlock));
-    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.ldy, p.rowptr, p.Y, unit, parts, quantum_log2, tile_log2,
+    DGSP_LAUNCH(nb_prepare_kernel, grid, p.M, p.N, p.ldy, p.rowptr, p.Y, parts, quantum_log2, tile_log2,
                 p.scaled ? p.beta : 0.0f);
     return DGSP_OK;
 }
@@ -266,7 +265,7 @@ int launch_nb_pr_v(const Problem& p) {
     if (col_groups > 65535u || p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
+        if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
         if (p.scaled)
             DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
@@ -300,7 +299,7 @@ int launch_nb_sr_v(const Problem& p) {
     if (p.scaled && !XBUF) return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, 0, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
+        if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
         if (p.scaled) {
             if constexpr (XBUF)

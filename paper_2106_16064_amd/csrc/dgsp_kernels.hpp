@@ -360,31 +360,26 @@ struct EvenSplit {
 
 // Zeroes the rows whose items do not all lie in one piece of the partition (beta != 0, the scaled
 // variants: multiplies them by beta instead, so that the partial sums added later land on beta * Y).
-// unit > 0: pieces are the multiples of `unit` items.  unit == 0: pieces are
-// the `parts` chunks of the even split with quanta of 2^quantum_log2 items, cut
-// further into tiles of 2^tile_log2 items counted from the chunk's start when
-// tile_log2 >= 0.
+// The pieces are the `parts` chunks of the even split with quanta of
+// 2^quantum_log2 items, cut further into tiles of 2^tile_log2 items counted
+// from the chunk's start when tile_log2 >= 0.
 // One thread per row for the test (split rows are few: at most two per piece);
 // a wave then clears its split rows together, 64 columns per store.
 __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ldy, const int* __restrict__ rowptr,
-                                                             float* __restrict__ Y, unsigned unit, unsigned parts,
-                                                             unsigned quantum_log2, int tile_log2, float beta) {
+                                                             float* __restrict__ Y, unsigned parts, unsigned quantum_log2,
+                                                             int tile_log2, float beta) {
     const long long row = (long long)blockIdx.x * kBlock + threadIdx.x;
     bool split = false;
     if (row < M) {
         const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
         const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
         if (first != last) {                                                 // an empty row is a single item
-            if (unit != 0) {
-                split = first / unit != last / unit;
-            } else {
-                const EvenSplit es((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
-                const unsigned c1 = es.chunk_of(first), c2 = es.chunk_of(last);
-                split = c1 != c2;
-                if (!split && tile_log2 >= 0) {
-                    const unsigned start = es.start(c1);
-                    split = (first - start) >> tile_log2 != (last - start) >> tile_log2;
-                }
+            const EvenSplit es((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
+            const unsigned c1 = es.chunk_of(first), c2 = es.chunk_of(last);
+            split = c1 != c2;
+            if (!split && tile_log2 >= 0) {
+                const unsigned start = es.start(c1);
+                split = (first - start) >> tile_log2 != (last - start) >> tile_log2;
             }
         }
     }
