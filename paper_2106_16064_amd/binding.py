@@ -322,6 +322,26 @@ class DeviceCsr:
         self.features = dgsp_features_from_csr_host(A.M, A.K, A.rowptr, A.colidx)
         self.tuned = {}        # N -> kernel found fastest by autotune()
 
+    @classmethod
+    def from_device(cls, M, K, rowptr, colidx, vals):
+        """Wraps CSR arrays that already live on the GPU (int32 ``rowptr`` / ``colidx``, float32 ``vals``; other
+        integer or float types are converted once).  The row statistics are computed on the device."""
+        import torch
+        self = cls.__new__(cls)
+        self.M, self.K = int(M), int(K)
+        self.rowptr = rowptr.to(torch.int32).contiguous()
+        self.colidx = colidx.to(torch.int32).contiguous()
+        self.vals = vals.to(torch.float32).contiguous()
+        self.nnz = int(self.colidx.numel())
+        self.features = dgsp_features_from_csr_device(self.M, self.K, self.rowptr, self.colidx if self.nnz else None)
+        self.tuned = {}
+        return self
+
+    @classmethod
+    def from_torch_sparse_csr(cls, t):
+        """From a ``torch.sparse_csr_tensor`` on the GPU."""
+        return cls.from_device(t.shape[0], t.shape[1], t.crow_indices(), t.col_indices(), t.values())
+
     def autotune(self, X, reps=5, Y=None):
         """Times the four kernels for this matrix and this width of X and remembers the winner:
         later ``spmm(X, algo=AUTO)`` calls with the same width use it instead of the rules."""

@@ -727,3 +727,22 @@ def test_plain_c_caller_of_the_library():
     print(res.stdout)
     assert res.returncode == 0, res.stdout + res.stderr
     assert res.stdout.count(" ok") == 5
+
+
+def test_matrix_that_is_already_on_the_device(dg):
+    """CSR arrays held by a torch sparse tensor (int64 indices) are taken over without a trip to the host:
+    statistics from the device pass, the adaptive call on top."""
+    import torch
+    A = wl.rmat_csr(scale=13, avg_degree=8, seed=77)
+    t = torch.sparse_csr_tensor(torch.from_numpy(A.rowptr.astype(np.int64)), torch.from_numpy(A.colidx.astype(np.int64)),
+                                torch.from_numpy(A.vals), size=(A.M, A.K)).cuda()
+    dA = dg.DeviceCsr.from_torch_sparse_csr(t)
+    host = dg.dgsp_features_from_csr_host(A.M, A.K, A.rowptr, A.colidx)
+    assert (dA.features.nnz, dA.features.max_row, dA.features.stdv_row, dA.features.col_span) == \
+           (host.nnz, host.max_row, host.stdv_row, host.col_span)
+    for N in (1, 8, 32):
+        X = wl.dense_matrix(A.K, N, "uniform", seed=N)
+        Y = dA.spmm(torch.from_numpy(X).cuda())
+        yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+        ok, worst = oracle.within_bound(Y.cpu().numpy(), yref, bnd, TOL)
+        assert ok, (N, worst)
