@@ -12,8 +12,8 @@ that every step streams its operands from HBM rather than from the 256 MB
 Infinity Cache (one copy of this workload, ~141 MB, would fit).  Prints ONE
 JSON line.
 
-Other suites (for the numbers quoted in the design doc / profiles/, each still
-prints one JSON line and writes details under gpurun_out/):
+Other suites (for the tables under profiles/; each still prints one JSON line
+and writes its per-cell records under RESULTS_DIR):
     --suite configs   every kernel on the R-MAT and stencil configurations
     --suite sweep     the 24-matrix x 10-N selector sweep (loss vs best kernel)
     --suite kernel --workload W --n N --algo A   one kernel in a loop (for rocprofv3)
@@ -38,6 +38,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CACHE_BYTES = 256e6 + 32e6     # Infinity Cache + 8 x 4 MB L2: what rotation has to exceed
+RESULTS_DIR = "gpurun_out"     # per-cell records of the suites
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on dgsp_copy_f32);
@@ -299,13 +300,13 @@ def run_headline(args):
 
 def run_configs(args):
     from paper_2106_16064_amd import binding as dg
-    os.makedirs("gpurun_out", exist_ok=True)
+    os.makedirs(RESULTS_DIR, exist_ok=True)
     cells = [("rmat_spmv", 1), ("rmat_spmv", 2), ("rmat_spmv", 4), ("rmat_gnn", 32), ("rmat_gnn", 64),
              ("rmat_gnn", 128), ("stencil", 1), ("stencil", 2), ("stencil", 4), ("stencil", 8)]
     if args.workload:
         cells = [c for c in cells if c[0] == args.workload]
     rows = []
-    path = os.path.join("gpurun_out", args.out or "bench_configs.jsonl")
+    path = os.path.join(RESULTS_DIR, args.out or "bench_configs.jsonl")
     with open(path, "w") as fh:
         for name, n in cells:
             A, X, label = make_workload(name, n)
@@ -331,8 +332,8 @@ def run_configs(args):
 def run_sweep(args):
     from paper_2106_16064_amd import binding as dg
     from paper_2106_16064_amd import workloads as wl
-    os.makedirs("gpurun_out", exist_ok=True)
-    path = os.path.join("gpurun_out", args.out or "bench_sweep.jsonl")
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_sweep.jsonl")
     M = args.sweep_m
     losses = []
     with open(path, "w") as fh:
@@ -404,8 +405,8 @@ def run_size(args):
     second launch of the balanced kernels starts to pay (fits the selector's pr_nnz_max)."""
     from paper_2106_16064_amd import binding as dg
     from paper_2106_16064_amd import workloads as wl
-    os.makedirs("gpurun_out", exist_ok=True)
-    path = os.path.join("gpurun_out", args.out or "bench_size.jsonl")
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_size.jsonl")
     gens = [(f"stencil27_n{n}", lambda n=n: wl.stencil27_csr(n, seed=0)) for n in (40, 64, 96, 128)]
     gens += [(f"fixed27_M2^{lg}", lambda lg=lg: wl.sweep_csr(1 << lg, 27, "fixed", 0)) for lg in (18, 19, 20, 21)]
     gens += [(f"poisson16_M2^{lg}", lambda lg=lg: wl.sweep_csr(1 << lg, 16, "poisson", 0)) for lg in (18, 20)]
@@ -438,8 +439,8 @@ def run_ablation(args):
     (Section 2.1.3)."""
     from paper_2106_16064_amd import binding as dg
     from paper_2106_16064_amd import workloads as wl
-    os.makedirs("gpurun_out", exist_ok=True)
-    path = os.path.join("gpurun_out", args.out or "bench_ablation.jsonl")
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_ablation.jsonl")
     skews = {"powerlaw": (0.57, 0.19, 0.19, 0.05), "mild": (0.45, 0.15, 0.15, 0.25), "uniform": (0.25, 0.25, 0.25, 0.25)}
     k = max(5, min(args.steps, 20))
 
@@ -496,10 +497,10 @@ THRESHOLD_NAMES = ("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min",
 
 def run_fit(args):
     """Grid-fits the selector thresholds.  Data: the seed-0 matrices of a finished sweep
-    (gpurun_out/bench_sweep.jsonl) plus, if that suite ran, the larger matrices of
-    gpurun_out/bench_size.jsonl (the sweep alone cannot place the size guard); checked on the
+    (bench_sweep.jsonl under RESULTS_DIR) plus, if that suite ran, the larger matrices of
+    bench_size.jsonl (the sweep alone cannot place the size guard); checked on the
     seed-1 matrices of the sweep.  No GPU needed."""
-    path = args.out or os.path.join("gpurun_out", "bench_sweep.jsonl")
+    path = args.out or os.path.join(RESULTS_DIR, "bench_sweep.jsonl")
     rows = [json.loads(l) for l in open(path)]
     size_path = os.path.join(os.path.dirname(path) or ".", "bench_size.jsonl")
     big = [json.loads(l) for l in open(size_path)] if os.path.exists(size_path) else []

@@ -88,3 +88,85 @@ def test_selector_sweep_matrices_at_full_size(dg, dist, mean, N):
     A = wl.sweep_csr(1 << 18, mean, dist, seed=1)
     heavy = A.row_lengths().max() > 2000
     run_cell(dg, A, wl.dense_matrix(A.K, N, "uniform", seed=N), (-1, 2, 3) if heavy else (-1, 0, 1, 2, 3))
+
+
+# ------------------------------------------------------------------ more than 2^30 stored entries
+BIG_M = BIG_K = 1 << 20
+
+
+def big_row_lengths(rows):
+    return 1024 + (rows % 512)
+
+
+def big_entries(rows):
+    """Columns and values of the given rows of the 1.34e9-entry matrix, from its closed form:
+    row i holds 1024 + i mod 512 entries; its j-th entry has column (977 i + 811 j) mod 2^20
+    (distinct within a row, not ascending) and value ((40503 p) mod 65536) / 65536 - 1/2 with
+    p the entry's position in the whole matrix.  Every step is exact in fp32 and in int64."""
+    rows = np.asarray(rows, dtype=np.int64)
+    lens = big_row_lengths(rows)
+    starts = 1024 * rows + 512 * 511 // 2 * (rows // 512) + (rows % 512) * (rows % 512 - 1) // 2
+    row_of = np.repeat(np.arange(rows.size), lens)
+    j = np.arange(int(lens.sum()), dtype=np.int64) - np.repeat(np.cumsum(lens) - lens, lens)
+    p = starts[row_of] + j
+    col = (977 * rows[row_of] + 811 * j) % BIG_K
+    val = ((40503 * p) % 65536).astype(np.float32) / np.float32(65536.0) - np.float32(0.5)
+    return lens, col.astype(np.int32), val
+
+
+def test_more_than_two_to_the_thirty_entries(dg):
+    """1.34e9 stored entries: the column and value arrays pass 4 GB each, so entry positions no longer
+    fit a 32-bit byte offset from the arrays' starts.  The matrix is written on the device from a
+    closed form; the oracle recomputes sampled rows from the same form on the host - among them the
+    rows around the 4 GB mark and the last ones."""
+    import torch
+    dev = torch.device("cuda:0")
+    rows = torch.arange(BIG_M, dtype=torch.int64, device=dev)
+    lens = 1024 + (rows % 512)
+    rowptr64 = torch.zeros(BIG_M + 1, dtype=torch.int64, device=dev)
+    rowptr64[1:] = torch.cumsum(lens, 0)
+    nnz = int(rowptr64[-1])
+    assert (1 << 30) < nnz < (1 << 31) - 4096
+    rowptr = rowptr64.to(torch.int32)
+    colidx = torch.empty(nnz, dtype=torch.int32, device=dev)
+    vals = torch.empty(nnz, dtype=torch.float32, device=dev)
+    step = 1 << 26
+    for lo in range(0, nnz, step):
+        p = torch.arange(lo, min(lo + step, nnz), dtype=torch.int64, device=dev)
+        i = torch.searchsorted(rowptr64, p, right=True) - 1
+        j = p - rowptr64[i]
+        colidx[lo:lo + p.numel()] = ((977 * i + 811 * j) % BIG_K).to(torch.int32)
+        vals[lo:lo + p.numel()] = ((40503 * p) % 65536).to(torch.float32) / 65536.0 - 0.5
+    del p, i, j, rows, lens
+    A = dg.DeviceCsr.from_device(BIG_M, BIG_K, rowptr, colidx, vals)
+    assert A.nnz == nnz and A.features.max_row == 1535 and A.features.min_row == 1024
+
+    # sampled rows: a seeded draw, the rows on both sides of byte 2^32 of the entry arrays, both ends
+    rp = rowptr64.cpu().numpy()
+    at_4g = int(np.searchsorted(rp, 1 << 30))
+    sample = np.unique(np.concatenate([
+        np.random.default_rng(5).integers(0, BIG_M, size=1500), np.arange(at_4g - 40, at_4g + 40),
+        np.arange(0, 70), np.arange(BIG_M - 70, BIG_M)]))
+    slens, scol, sval = big_entries(sample)
+    assert np.array_equal(slens, np.diff(rp)[sample])
+    # the device arrays hold what the closed form says (bit for bit) on the sampled rows
+    first = sample[len(sample) // 2]
+    a, b = int(rp[first]), int(rp[first + 1])
+    l1, c1, v1 = big_entries([first])
+    assert np.array_equal(colidx[a:b].cpu().numpy(), c1) and np.array_equal(vals[a:b].cpu().numpy(), v1)
+    srowptr = np.zeros(sample.size + 1, dtype=np.int32)
+    srowptr[1:] = np.cumsum(slens)
+
+    for N, algos in ((1, (-1, 3, 2, 1, 0)), (4, (-1, 2, 0))):
+        X = wl.dense_matrix(BIG_K, N, "uniform", seed=40 + N)
+        yref, bnd = oracle.spmm_ref(sample.size, BIG_K, N, srowptr, scol, sval, X)
+        dX = torch.from_numpy(X).cuda()
+        for algo in algos:
+            print(f"[case] 1.34e9 entries N={N} algo={NAMES[algo]}", flush=True)
+            dY = torch.full((BIG_M, N), float("nan"), device=dev)
+            A.spmm(dX, algo=algo, Y=dY)
+            torch.cuda.synchronize()
+            assert not bool(torch.isnan(dY).any())
+            Y = dY[torch.from_numpy(sample).cuda()].cpu().numpy()
+            ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+            assert ok, f"{NAMES[algo]} N={N}: worst |err|/bound {worst:.3e}"
