@@ -1,0 +1,107 @@
+"""GPU parity on a seeded stream of random small problems: shapes, row-length laws, dense widths, leading
+dimensions, view offsets and scale factors drawn together, every kernel and the adaptive call on each, against
+the CPU oracle.  Complements the hand-picked cases: combinations nobody thought of.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2106_16064_amd import workloads as wl
+
+TOL = 1e-5
+WIDTHS = (1, 1, 2, 2, 3, 4, 4, 5, 7, 8, 8, 12, 16, 24, 31, 32, 33, 64, 65, 100, 128, 130, 256, 300)
+
+
+def random_row_lengths(rng, M, K):
+    law = rng.integers(0, 7)
+    if law == 0:                                                   # Poisson
+        lens = rng.poisson(rng.choice([0.3, 2.0, 9.0, 40.0]), size=M)
+    elif law == 1:                                                 # heavy tail
+        lens = np.floor(rng.pareto(1.2, size=M) * rng.choice([1.0, 6.0])).astype(np.int64)
+    elif law == 2:                                                 # all rows alike
+        lens = np.full(M, rng.choice([1, 2, 7, 27, 63, 64, 65, 130]))
+    elif law == 3:                                                 # long empty stretches, short bursts
+        lens = np.zeros(M, dtype=np.int64)
+        hot = rng.random(M) < 0.02
+        lens[hot] = rng.integers(1, 20, size=int(hot.sum()))
+    elif law == 4:                                                 # one row that dwarfs the rest
+        lens = rng.poisson(3.0, size=M)
+        lens[rng.integers(0, M)] = rng.choice([500, 3000, 20000])
+    elif law == 5:                                                 # lengths around the wave and tile widths
+        lens = rng.choice([0, 1, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1024, 1025], size=M)
+    else:                                                          # nothing stored in the first or the last part
+        lens = rng.poisson(5.0, size=M)
+        cut = rng.integers(0, M + 1)
+        if rng.random() < 0.5: lens[:cut] = 0
+        else: lens[cut:] = 0
+    return np.minimum(lens, K).astype(np.int64), int(law)
+
+
+def random_case(seed):
+    rng = np.random.default_rng([seed, 0xf022])
+    M = int(np.exp(rng.uniform(0.0, np.log(20000.0))))
+    K = int(np.exp(rng.uniform(0.0, np.log(20000.0))))
+    lens, law = random_row_lengths(rng, M, K)
+    if lens.sum() > 400_000:                                       # keep the oracle and the row-split kernels quick
+        lens = np.minimum(lens, max(1, 400_000 // M))
+    N = int(rng.choice(WIDTHS))
+    ldx = N + int(rng.choice([0, 0, 1, 3, 4, 60]))
+    ldy = N + int(rng.choice([0, 0, 1, 3, 4, 28]))
+    x0 = int(rng.integers(0, ldx - N + 1))
+    y0 = int(rng.integers(0, ldy - N + 1))
+    scale = None
+    if rng.random() < 0.35:
+        scale = (float(rng.choice([1.0, -2.0, 0.5, 0.0])), float(rng.choice([0.0, 1.0, -0.25])))
+    return dict(seed=seed, M=M, K=K, law=law, lens=lens, N=N, ldx=ldx, ldy=ldy, x0=x0, y0=y0, scale=scale)
+
+
+def test_random_cases_are_what_they_claim():
+    """The generator is deterministic and covers what it is meant to (runs without a GPU too)."""
+    a, b = random_case(7), random_case(7)
+    assert a["M"] == b["M"] and np.array_equal(a["lens"], b["lens"]) and a["N"] == b["N"]
+    cases = [random_case(s) for s in range(160)]
+    assert {c["law"] for c in cases} == set(range(7))
+    assert any(c["scale"] is not None for c in cases) and any(c["ldx"] > c["N"] for c in cases)
+    assert any(c["M"] < 8 for c in cases) and any(c["M"] > 3000 for c in cases)
+    assert all(c["lens"].max(initial=0) <= c["K"] for c in cases)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("block", range(16))
+def test_random_problems(block):
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    dg.lib()
+    for seed in range(block * 50, block * 50 + 50):
+        c = random_case(seed)
+        M, K, N, ldx, ldy, x0, y0 = c["M"], c["K"], c["N"], c["ldx"], c["ldy"], c["x0"], c["y0"]
+        A = wl.csr_from_lens(c["lens"], K, seed=seed, name=f"random{seed}")
+        rng = np.random.default_rng([seed, 1])
+        Xw = rng.standard_normal((K, ldx)).astype(np.float32)
+        Y0 = rng.uniform(-1.0, 1.0, size=(M, ldy)).astype(np.float32)
+        Xs = np.ascontiguousarray(Xw[:, x0:x0 + N])
+        yref, bnd = oracle.spmm_ref(M, K, N, A.rowptr, A.colidx, A.vals, Xs)
+        alpha, beta = c["scale"] if c["scale"] is not None else (1.0, 0.0)
+        want = alpha * yref + (beta * Y0[:, y0:y0 + N].astype(np.float64) if beta != 0.0 else 0.0)
+        bound = abs(alpha) * bnd + abs(beta) * np.abs(Y0[:, y0:y0 + N].astype(np.float64))
+        dA = dg.DeviceCsr(A)
+        dXw = torch.from_numpy(Xw).cuda()
+        outside = np.ones(ldy, dtype=bool); outside[y0:y0 + N] = False
+        for algo in (0, 1, 2, 3, dg.AUTO):
+            print(f"[case] seed={seed} M={M} K={K} nnz={A.nnz} law={c['law']} N={N} ldx={ldx} ldy={ldy} x0={x0} "
+                  f"y0={y0} scale={c['scale']} algo={algo}", flush=True)
+            dYw = torch.from_numpy(Y0).cuda()
+            if beta == 0.0:
+                dYw[:, y0:y0 + N] = float("nan")                       # must be overwritten, never read
+            args = (M, K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dXw[:, x0:x0 + N], dYw[:, y0:y0 + N])
+            if c["scale"] is not None:
+                dg.dgsp_spmm_csr_axpby(*args, alpha, beta, algo, dA.features)
+            else:
+                dg.dgsp_spmm_csr_ld(*args, algo, dA.features)
+            torch.cuda.synchronize()
+            Yw = dYw.cpu().numpy()
+            Y = Yw[:, y0:y0 + N]
+            assert not np.isnan(Y).any(), f"seed {seed} algo {algo}: outputs never written"
+            ok, worst = oracle.within_bound(Y, want, bound, 2e-5 if c["scale"] is not None else TOL)
+            assert ok, f"seed {seed} algo {algo}: worst |err|/bound = {worst:.3e}"
+            assert np.array_equal(Yw[:, outside], Y0[:, outside]), f"seed {seed} algo {algo}: wrote outside the slice"
