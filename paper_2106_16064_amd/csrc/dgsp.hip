@@ -145,10 +145,10 @@ int launch_rs_pr(const Problem& p) {
 }
 
 // lanes per row of the sequential kernels: enough lanes of width V to span N, at most a wave
-inline int sr_lanes_log2(long long N, int V) {
+inline int sr_lanes_log2(long long N, int V, int cap = 6) {
     const long long need = (N + V - 1) / V;
     const int lg = ilog2_ceil(need);
-    return lg > 6 ? 6 : lg;
+    return lg > cap ? cap : lg;
 }
 
 // Dense-row loads in flight per lane of the sequential kernels: enough to fill, not to overflow,
@@ -289,7 +289,11 @@ int launch_nb_pr(const Problem& p) {
 
 template <int V, bool XBUF, int DEPTH>
 int launch_nb_sr_v(const Problem& p) {
-    const int logG = sr_lanes_log2(p.N, V);
+    // Column blocks of at most 64 dense columns (256 bytes of a row of X): wider N runs as several blocks over
+    // the same chunks, one after the other in launch order.  The rows of X that many matrix rows share (hub
+    // columns of a power-law graph) then compete for the L2 with a quarter-kilobyte each instead of N * 4
+    // bytes; re-reading the 8 bytes of an entry per block costs 3 % of what the block gathers for it.
+    const int logG = sr_lanes_log2(p.N, V, V == 4 ? 4 : V == 2 ? 5 : 6);
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
