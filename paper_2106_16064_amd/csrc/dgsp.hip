@@ -61,6 +61,16 @@ constexpr int kBlocksPerCu = 8;
 
 static_assert((1 << kNbSrLogTile) == kNbSrTile, "tile must be a power of two");
 
+extern dgsp_thresholds_t g_thresholds;      // the selector's state, defined further down
+
+// What a caller's row statistics tell the launch code (nothing, when it passed none).
+struct Hints {
+    double col_span = 0.0;
+    double cv_row = -1.0;
+    Hints() = default;
+    explicit Hints(const dgsp_features_t* f) { if (f) { col_span = f->col_span; cv_row = f->cv_row; } }
+};
+
 struct Problem {
     int M, N;
     int ldx, ldy;       // leading dimensions of X and Y in elements (>= N)
@@ -69,6 +79,7 @@ struct Problem {
     hipStream_t stream;
     int phase = DGSP_PHASE_ALL;
     double col_span = 0.0;   // mean column span of a row / K; 0 = unknown
+    double cv_row = -1.0;    // coefficient of variation of the row lengths; < 0 = unknown
     int switches = 0;        // DGSP_ABL_* (measurement aids)
     bool scaled = false;     // Y = alpha * A X + beta * Y instead of Y = A X
     float alpha = 1.0f, beta = 0.0f;
@@ -158,7 +169,12 @@ inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 
 
 template <int V, bool XBUF, int DEPTH>
 int launch_rs_sr_v(const Problem& p) {
-    const int logG = sr_lanes_log2(p.N, V);
+    // Rows of about equal length (what the selection rules send here): column blocks of at most 64 dense columns
+    // as in the balanced kernel, four or more rows per wave in step; 2-16 % faster at N >= 128 on such matrices.
+    // With long rows among short ones the rows of a wave wait for the longest (+30 % measured), and without row
+    // statistics nothing is known: then a group spans the whole width.
+    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= g_thresholds.sr_cv_min;
+    const int logG = sr_lanes_log2(p.N, V, even_rows ? (V == 4 ? 4 : V == 2 ? 5 : 6) : 6);
     const long long cols_per_block = (long long)V << logG;
     const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
@@ -347,7 +363,7 @@ dgsp_thresholds_t g_thresholds = {
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
         const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
-        double col_span = 0.0, int switches = 0, int64_t ldx = -1, int64_t ldy = -1, const Scaling* scaling = nullptr) {
+        Hints hints = Hints(), int switches = 0, int64_t ldx = -1, int64_t ldy = -1, const Scaling* scaling = nullptr) {
     if (M < 0 || K < 0 || N < 0) return DGSP_ERR_INVALID_ARG;
     if (ldx < 0) ldx = N;            // packed rows unless the caller says otherwise
     if (ldy < 0) ldy = N;
@@ -362,7 +378,7 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
 
     if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
 
-    Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, col_span, switches};
+    Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, hints.col_span, hints.cv_row, switches};
     if (scaling) { p.scaled = true; p.alpha = scaling->alpha; p.beta = scaling->beta; }
     switch (algo) {
         case DGSP_RS_SR: return phase == DGSP_PHASE_PREPARE ? DGSP_OK : launch_rs_sr(p);
@@ -394,7 +410,7 @@ extern "C" int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
     if (phase < DGSP_PHASE_ALL || phase > DGSP_PHASE_MAIN) return DGSP_ERR_INVALID_ARG;
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, phase,
-               features ? features->col_span : 0.0);
+               Hints(features));
 }
 
 extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
@@ -409,7 +425,7 @@ extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, co
             algo = DGSP_NB_SR;        // the eight-column rule needs 16-byte accesses
     }
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
-               features ? features->col_span : 0.0, 0, ldx, ldy);
+               Hints(features), 0, ldx, ldy);
 }
 
 extern "C" int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
@@ -426,7 +442,7 @@ extern "C" int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
     }
     const Scaling sc{alpha, beta};
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
-               features ? features->col_span : 0.0, 0, ldx, ldy, &sc);
+               Hints(features), 0, ldx, ldy, &sc);
 }
 
 extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
@@ -437,7 +453,7 @@ extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t n
     if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
-               features ? features->col_span : 0.0, switches);
+               Hints(features), switches);
 }
 
 extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_features_t* features,
@@ -449,7 +465,7 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
     if (algo < 0) return DGSP_ERR_INVALID_ARG;
     if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max && widest_vector(N, X, Y) < 4) algo = DGSP_NB_SR;
     if (chosen) *chosen = algo;
-    return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, features->col_span);
+    return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, Hints(features));
 }
 
 // Section 2.2: N picks the reduction, row-length statistics pick the partition.
@@ -586,7 +602,7 @@ extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const
     if (reps < 1) reps = 1;
     if (reps > 100) reps = 100;
     if (features && nnz < 0) nnz = features->nnz;
-    const double col_span = features ? features->col_span : 0.0;
+    const Hints hints(features);
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return DGSP_ERR_LAUNCH;
@@ -601,7 +617,7 @@ extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const
         for (int r = 0; r <= reps; ++r) {
             if (r > 0 && hipEventRecord(e0, st) != hipSuccess) { rc = DGSP_ERR_LAUNCH; break; }
             const int one = run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
-                                col_span);
+                                hints);
             if (one == DGSP_ERR_UNSUPPORTED) break;            // this kernel does not take the shape: skip it
             if (one != DGSP_OK) { rc = one; break; }
             if (r == 0) continue;

@@ -151,7 +151,8 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
     }
 }
 
-template <int V>
+// AUX 2 marks the store non-temporal (the line need not stay in the L2).
+template <int V, int AUX = 0>
 __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
     if constexpr (V == 8) {
         typedef float f4 __attribute__((ext_vector_type(4)));
@@ -159,20 +160,20 @@ __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, un
         const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 16u;
         const f4 t = {x[0], x[1], x[2], x[3]};
         const f4 u = {x[4], x[5], x[6], x[7]};
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, u), rsrc, second, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, AUX);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, u), rsrc, second, 0, AUX);
     } else if constexpr (V == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
         const f4 t = {x[0], x[1], x[2], x[3]};
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, AUX);
     } else if constexpr (V == 2) {
         typedef float f2 __attribute__((ext_vector_type(2)));
         typedef unsigned u2 __attribute__((ext_vector_type(2)));
         const f2 t = {x[0], x[1]};
-        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, AUX);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, AUX);
     }
 }
 
