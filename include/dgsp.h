@@ -131,8 +131,11 @@ typedef struct {
  *             any row-length distribution).
  *   stream    hipStream_t as void*, NULL = default stream.
  *
- * Every algo accepts every N >= 1 and any pointer alignment; vector loads of
- * width v in {4, 2} are used when N % v == 0 and X, Y are 4v-byte aligned.
+ * Every algo accepts every N >= 1 and any (float) alignment of X and Y.  The
+ * parallel-reduction kernels use vector loads of width v in {4, 2} when N and
+ * the leading dimensions are multiples of v and X, Y are 4v-byte aligned, and
+ * one pass per v columns; the sequential-reduction kernels give a lane four
+ * columns for every N >= 4 at any alignment (two for N = 2, 3).
  * M == 0 or N == 0: returns DGSP_OK without launching.  The number of stored
  * entries is read on the device from rowptr[M]; the call never synchronises.
  */

@@ -162,21 +162,57 @@ inline int sr_lanes_log2(long long N, int V, int cap = 6) {
     return lg > cap ? cap : lg;
 }
 
+// Column blocks of the sequential kernels.  A group of G lanes (a power of two) walks the entries once per block,
+// so a call costs about blocks * G lane-steps per entry, and every further pass over the matrix costs more than
+// its share (measured +15 ... +33 % per extra pass at equal blocks * G).  The blocks are made equally wide (three
+// blocks for N = 300 are 100 + 100 + 100, not 128 + 128 + 44).  `narrow`: N is a multiple of 64 and the caller
+// wants blocks of 64 columns, all lanes busy in every block (see the launch functions for when that pays).
+struct SrColumns { int logG; int cols_per_block; unsigned blocks; };
+inline SrColumns sr_columns(long long N, int V, bool narrow) {
+    const long long lanes = (N + V - 1) / V;
+    long long blocks = 1;
+    if (narrow && N % 64 == 0) {
+        blocks = N / 64;
+    } else {
+        double best = 0.0;
+        for (int lg = 0; lg <= 6; ++lg) {
+            const long long b = (lanes + (1ll << lg) - 1) >> lg;
+            const double cost = (double)(b << lg) * (1.0 + 0.3 * (double)(b - 1));
+            if (lg == 0 || cost <= best) { best = cost; blocks = b; }         // ties: the wider group, fewer passes
+        }
+    }
+    const long long per = (((N + blocks - 1) / blocks + V - 1) / V) * V;        // a multiple of V
+    return {sr_lanes_log2(per, V), (int)per, (unsigned)((N + per - 1) / per)};
+}
+
 // Dense-row loads in flight per lane of the sequential kernels: enough to fill, not to overflow,
 // the L1 when rows of X are scattered (about 1 KB per wave: 4 / V loads), four when the matrix is
 // known to be banded (neighbouring rows then share their rows of X and mostly hit in cache).
 inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 0.05; }
 
-template <int V, bool XBUF, int DEPTH>
+// The sequential kernels give a lane four dense columns whenever a row has four (two when it has two or
+// three): the memory pipeline takes dwordx2 / dwordx4 accesses at any dword address, so neither the alignment
+// of X and Y nor their leading dimensions restrict the width.  When N is not a multiple of it the last lane of a
+// row takes the row's last columns and leaves out those it shares with its neighbour (RAGGED).
+struct SrShape { int v; bool ragged; };
+inline SrShape sr_shape(const Problem& p) {
+    if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return {1, false};
+    const int v = p.N >= 4 ? 4 : p.N >= 2 ? 2 : 1;
+    return {v, p.N % v != 0};
+}
+// dense-row loads in flight per lane (see banded())
+template <int V> constexpr int sr_depth_scattered() { return V == 4 ? 1 : V == 2 ? 2 : 4; }
+
+template <int V, bool XBUF, int DEPTH, bool RAGGED>
 int launch_rs_sr_v(const Problem& p) {
-    // Rows of about equal length (what the selection rules send here): column blocks of at most 64 dense columns
-    // as in the balanced kernel, four or more rows per wave in step; 2-16 % faster at N >= 128 on such matrices.
+    // Rows of about equal length (what the selection rules send here) and N a multiple of 64: column blocks of 64
+    // dense columns as in the balanced kernel, four rows per wave in step; 2-16 % faster at N >= 128 on such matrices.
     // With long rows among short ones the rows of a wave wait for the longest (+30 % measured), and without row
     // statistics nothing is known: then a group spans the whole width.
     const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= g_thresholds.sr_cv_min;
-    const int logG = sr_lanes_log2(p.N, V, even_rows ? (V == 4 ? 4 : V == 2 ? 5 : 6) : 6);
-    const long long cols_per_block = (long long)V << logG;
-    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    const SrColumns cols = sr_columns(p.N, V, even_rows && p.N >= 128);
+    const int logG = cols.logG;
+    const unsigned col_blocks = cols.blocks;
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int rows_per_wave = kWave >> logG;
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
@@ -184,14 +220,15 @@ int launch_rs_sr_v(const Problem& p) {
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
     if (p.scaled) {
         if constexpr (XBUF) {
-            DGSP_LAUNCH((rs_sr_kernel<V, true, DEPTH, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals,
-                        p.X, p.Y, logG, Scaling{p.alpha, p.beta});
+            DGSP_LAUNCH((rs_sr_kernel<V, true, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals,
+                        p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
             return DGSP_OK;
         } else {
             return DGSP_ERR_UNSUPPORTED;
         }
     }
-    DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
+                p.Y, logG, cols.cols_per_block);
     return DGSP_OK;
 }
 
@@ -209,6 +246,14 @@ int launch_rs_sr_direct_v(const Problem& p) {
     return DGSP_OK;
 }
 
+template <int V, bool RAGGED>
+int launch_rs_sr_pick(const Problem& p) {
+    const bool xb = x_fits_descriptor(p);
+    if (banded(p)) return xb ? launch_rs_sr_v<V, true, 4, RAGGED>(p) : launch_rs_sr_v<V, false, 4, RAGGED>(p);
+    constexpr int D = sr_depth_scattered<V>();
+    return xb ? launch_rs_sr_v<V, true, D, RAGGED>(p) : launch_rs_sr_v<V, false, D, RAGGED>(p);
+}
+
 int launch_rs_sr(const Problem& p) {
     if (p.switches & DGSP_ABL_NO_SPARSE_STAGING) {
         switch (vector_width(p)) {
@@ -217,15 +262,11 @@ int launch_rs_sr(const Problem& p) {
             default: return launch_rs_sr_direct_v<1>(p);
         }
     }
-    const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p)) {
-        case 4:
-            if (banded(p)) return xb ? launch_rs_sr_v<4, true, 4>(p) : launch_rs_sr_v<4, false, 4>(p);
-            return xb ? launch_rs_sr_v<4, true, 1>(p) : launch_rs_sr_v<4, false, 1>(p);
-        case 2:
-            if (banded(p)) return xb ? launch_rs_sr_v<2, true, 4>(p) : launch_rs_sr_v<2, false, 4>(p);
-            return xb ? launch_rs_sr_v<2, true, 2>(p) : launch_rs_sr_v<2, false, 2>(p);
-        default: return xb ? launch_rs_sr_v<1, true, 4>(p) : launch_rs_sr_v<1, false, 4>(p);
+    const SrShape shape = sr_shape(p);
+    switch (shape.v) {
+        case 4: return shape.ragged ? launch_rs_sr_pick<4, true>(p) : launch_rs_sr_pick<4, false>(p);
+        case 2: return shape.ragged ? launch_rs_sr_pick<2, true>(p) : launch_rs_sr_pick<2, false>(p);
+        default: return launch_rs_sr_pick<1, false>(p);
     }
 }
 
@@ -303,46 +344,50 @@ int launch_nb_pr(const Problem& p) {
     }
 }
 
-template <int V, bool XBUF, int DEPTH>
+template <int V, bool XBUF, int DEPTH, bool RAGGED>
 int launch_nb_sr_v(const Problem& p) {
-    // Column blocks of at most 64 dense columns (256 bytes of a row of X): wider N runs as several blocks over
+    // N a multiple of 64: column blocks of 64 dense columns (256 bytes of a row of X), several blocks over
     // the same chunks, one after the other in launch order.  The rows of X that many matrix rows share (hub
     // columns of a power-law graph) then compete for the L2 with a quarter-kilobyte each instead of N * 4
     // bytes; re-reading the 8 bytes of an entry per block costs 3 % of what the block gathers for it.
-    const int logG = sr_lanes_log2(p.N, V, V == 4 ? 4 : V == 2 ? 5 : 6);
-    const long long cols_per_block = (long long)V << logG;
-    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    const SrColumns cols = sr_columns(p.N, V, p.N >= 128);
+    const int logG = cols.logG;
+    const unsigned col_blocks = cols.blocks;
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
     if (p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     if (p.scaled && !XBUF) return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
-    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH>), false, col_blocks), col_blocks);
+    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
         if (p.scaled) {
             if constexpr (XBUF)
-                DGSP_LAUNCH((nb_sr_kernel<V, true, DEPTH, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
-                            p.vals, p.X, p.Y, logG, Scaling{p.alpha, p.beta});
+                DGSP_LAUNCH((nb_sr_kernel<V, true, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
+                            p.vals, p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
         } else {
-            DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
-                        logG);
+            DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
+                        logG, cols.cols_per_block);
         }
     }
     return DGSP_OK;
 }
 
-int launch_nb_sr(const Problem& p) {
+template <int V, bool RAGGED>
+int launch_nb_sr_pick(const Problem& p) {
     const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p)) {
-        case 4:
-            if (banded(p)) return xb ? launch_nb_sr_v<4, true, 4>(p) : launch_nb_sr_v<4, false, 4>(p);
-            return xb ? launch_nb_sr_v<4, true, 1>(p) : launch_nb_sr_v<4, false, 1>(p);
-        case 2:
-            if (banded(p)) return xb ? launch_nb_sr_v<2, true, 4>(p) : launch_nb_sr_v<2, false, 4>(p);
-            return xb ? launch_nb_sr_v<2, true, 2>(p) : launch_nb_sr_v<2, false, 2>(p);
-        default: return xb ? launch_nb_sr_v<1, true, 4>(p) : launch_nb_sr_v<1, false, 4>(p);
+    if (banded(p)) return xb ? launch_nb_sr_v<V, true, 4, RAGGED>(p) : launch_nb_sr_v<V, false, 4, RAGGED>(p);
+    constexpr int D = sr_depth_scattered<V>();
+    return xb ? launch_nb_sr_v<V, true, D, RAGGED>(p) : launch_nb_sr_v<V, false, D, RAGGED>(p);
+}
+
+int launch_nb_sr(const Problem& p) {
+    const SrShape shape = sr_shape(p);
+    switch (shape.v) {
+        case 4: return shape.ragged ? launch_nb_sr_pick<4, true>(p) : launch_nb_sr_pick<4, false>(p);
+        case 2: return shape.ragged ? launch_nb_sr_pick<2, true>(p) : launch_nb_sr_pick<2, false>(p);
+        default: return launch_nb_sr_pick<1, false>(p);
     }
 }
 

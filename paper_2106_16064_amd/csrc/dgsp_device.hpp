@@ -88,6 +88,20 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x
     }
 }
 
+// The same for global addresses that are only known to be dword aligned (rows of a matrix whose leading
+// dimension is not a multiple of V): still one dwordx2 / dwordx4 access, which the memory pipeline takes at
+// any dword address; the compiler is merely told not to assume more.
+template <int V>
+__device__ __forceinline__ void load_vec_dword_aligned(const float* __restrict__ p, float (&x)[V]) {
+    static_assert(V == 1 || V == 2 || V == 4, "one access");
+    __builtin_memcpy(&x[0], p, sizeof(float) * V);
+}
+template <int V>
+__device__ __forceinline__ void store_vec_dword_aligned(float* __restrict__ p, const float (&x)[V]) {
+    static_assert(V == 1 || V == 2 || V == 4, "one access");
+    __builtin_memcpy(p, &x[0], sizeof(float) * V);
+}
+
 // Hardware fp32 add at the L2 (global_atomic_add_f32, no return value).
 template <int V>
 __device__ __forceinline__ void atomic_add_vec(float* p, const float (&x)[V]) {
@@ -180,11 +194,11 @@ __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, un
 // Scaling of a finished result (the kernels' AXPBY variants): v = alpha * v + beta * old.  With
 // beta == 0 the old value is not read, so the output buffer may hold anything beforehand.
 struct Scaling { float alpha, beta; };
-template <int V>
+template <int V, bool DWORD_ALIGNED = false>
 __device__ __forceinline__ void scale_into(float (&v)[V], const float* __restrict__ old, Scaling s) {
     if (s.beta != 0.0f) {
         float o[V];
-        load_vec<V>(old, o);
+        if constexpr (DWORD_ALIGNED) load_vec_dword_aligned<V>(old, o); else load_vec<V>(old, o);
 #pragma unroll
         for (int i = 0; i < V; ++i) v[i] = fmaf(s.alpha, v[i], s.beta * o[i]);
     } else {
@@ -212,6 +226,48 @@ __device__ __forceinline__ int buffer_stream_i32(__amdgpu_buffer_rsrc_t r, unsig
 }
 __device__ __forceinline__ float buffer_stream_f32(__amdgpu_buffer_rsrc_t r, unsigned byte_offset) {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, byte_offset, 0, 2));
+}
+
+// ---------------------------------------------------------------------------
+// the V dense columns of a lane in the sequential-reduction kernels
+// ---------------------------------------------------------------------------
+// Column block `block` covers `cols_per_block` columns (a multiple of V, at most G * V) from block * cols_per_block;
+// lane `gl` of a group normally owns [first, first + V) with first = block * cols_per_block + gl * V.  RAGGED (N is
+// not a multiple of V, N >= V): the lane whose window would pass N takes the last V columns of the row instead, so
+// that every load stays inside the row; `skip` of them also belong to its left neighbour, which computes the same
+// sums from the same entries in the same order - the lane keeps them out of everything it writes.
+struct LaneColumns {
+    long long first;    // first column of the window
+    int skip;           // leading columns of the window that are the neighbour's (0 < skip < V on one lane at most)
+    bool any;           // the lane has columns at all
+};
+template <int V, bool RAGGED>
+__device__ __forceinline__ LaneColumns lane_columns(unsigned block, int cols_per_block, int gl, int N) {
+    LaneColumns c;
+    c.first = (long long)block * cols_per_block + gl * V;
+    c.skip = 0;
+    c.any = gl * V < cols_per_block && c.first < N;
+    if constexpr (RAGGED) {
+        if (c.any && c.first + V > N) { c.skip = (int)(c.first + V - N); c.first = (long long)N - V; }
+    }
+    return c;
+}
+
+// Stores a lane's V results at byte_offset (kOutOfRange: nothing), leaving out its first `skip`.
+template <int V, bool RAGGED, int AUX = 0>
+__device__ __forceinline__ void buffer_store_columns(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V],
+                                                     int skip) {
+    if constexpr (!RAGGED) {
+        buffer_store_vec<V, AUX>(rsrc, byte_offset, x);
+    } else {
+        buffer_store_vec<V, AUX>(rsrc, skip == 0 ? byte_offset : kOutOfRange, x);
+#pragma unroll
+        for (int i = 1; i < V; ++i) {                       // at most one lane of a group takes this part
+            const float one[1] = {x[i]};
+            const bool on = skip != 0 && i >= skip && byte_offset != kOutOfRange;
+            buffer_store_vec<1, AUX>(rsrc, on ? byte_offset + 4u * (unsigned)i : kOutOfRange, one);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

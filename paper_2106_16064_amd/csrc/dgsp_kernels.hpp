@@ -167,12 +167,12 @@ constexpr int kRsSrTile = 512;   // cached pairs per wave and round
 // at depth 4).  Rows that hit in cache anyway want the latency hidden instead (27-point stencil,
 // N = 8: 204 us at depth 4, 260 us at depth 1), and so do rows of uneven length.  The host picks.
 
-template <int V, bool XBUF, int DEPTH, bool AXPBY = false>
+template <int V, bool XBUF, int DEPTH, bool AXPBY = false, bool RAGGED = false>
 __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG, Scaling sc = Scaling{1.0f, 0.0f}) {
+                                                        int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int T = kRsSrTile;
     __shared__ int s_col[kWavesPerBlock][T];
     __shared__ float s_val[kWavesPerBlock][T];
@@ -185,8 +185,9 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
     const int g = lane >> logG;
     const int rows_per_wave = kWave >> logG;
 
-    const long long n = ((long long)blockIdx.y * G + gl) * V;   // my first dense column
-    const bool col_ok = n < N;
+    const LaneColumns mine = lane_columns<V, RAGGED>(blockIdx.y, cols_per_block, gl, N);
+    const long long n = mine.first;                              // my first dense column
+    const bool col_ok = mine.any;
 
     const unsigned nwaves = gridDim.x * kWavesPerBlock;
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wib;
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
                         if constexpr (XBUF) {
                             buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
                         } else {
-                            load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + n, x[u]);
+                            load_vec_dword_aligned<V>(X + (size_t)(ok ? c : 0u) * ldx + n, x[u]);
 #pragma unroll
                             for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
                         }
@@ -253,8 +254,14 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
         }
         if (live && col_ok) {
             float* y = Y + (size_t)row * ldy + n;
-            if constexpr (AXPBY) scale_into<V>(acc, y, sc);
-            store_vec<V>(y, acc);
+            if constexpr (AXPBY) scale_into<V, true>(acc, y, sc);
+            if (RAGGED && mine.skip != 0) {
+#pragma unroll
+                for (int i = 1; i < V; ++i)
+                    if (i >= mine.skip) y[i] = acc[i];
+            } else {
+                store_vec_dword_aligned<V>(y, acc);
+            }
         }
     }
 }
@@ -769,12 +776,12 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 constexpr int kNbSrTile = 512;
 constexpr int kNbSrLogTile = 9;
 
-template <int V, bool XBUF, int DEPTH, bool AXPBY = false>
+template <int V, bool XBUF, int DEPTH, bool AXPBY = false, bool RAGGED = false>
 __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG, Scaling sc = Scaling{1.0f, 0.0f}) {
+                                                        int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int W = kNbSrTile;
     constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
     __shared__ int s_col[kWavesPerBlock][W];
@@ -798,8 +805,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const int groups = kWave >> logG;
     const int logU = kNbSrLogTile - 6 + logG;
     const unsigned U = 1u << logU;
-    const long long n = ((long long)blockIdx.y * G + gl) * V;
-    const bool col_ok = n < N;
+    const LaneColumns mine = lane_columns<V, RAGGED>(blockIdx.y, cols_per_block, gl, N);
+    const long long n = mine.first;
+    const bool col_ok = mine.any;
 
     const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
@@ -893,9 +901,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                         for (int i = 0; i < V; ++i) out[i] = 0.0f;
                         scale_into<V>(out, yrows, off, sc);               // beta * Y
-                        buffer_store_vec<V, 2>(yrows, off, out);
+                        buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip);
                     } else {
-                        buffer_store_vec<V, 2>(yrows, off, zero);
+                        buffer_store_columns<V, RAGGED, 2>(yrows, off, zero, mine.skip);
                     }
                 }
             }
@@ -964,9 +972,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                     for (int i = 0; i < V; ++i) out[i] = acc[i];
                     scale_into<V>(out, yrows, off, sc);
-                    buffer_store_vec<V, 2>(yrows, off, out);
+                    buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip);
                 } else {
-                    buffer_store_vec<V, 2>(yrows, off, acc);
+                    buffer_store_columns<V, RAGGED, 2>(yrows, off, acc, mine.skip);
                 }
                 if (closing) {
                     if (!direct) to_slot(true);
@@ -989,7 +997,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
             if constexpr (XBUF) {
                 buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + n_bytes : kOutOfRange, x[u]);
             } else {
-                load_vec<V>(X + (size_t)(ok ? c : 0u) * ldx + (col_ok ? n : 0), x[u]);
+                load_vec_dword_aligned<V>(X + (size_t)(ok ? c : 0u) * ldx + (col_ok ? n : 0), x[u]);
 #pragma unroll
                 for (int i = 0; i < V; ++i) x[u][i] = ok ? x[u][i] : 0.0f;
             }
@@ -1024,13 +1032,22 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                     const bool whole = s > 0 && slot_end[s];
                     if constexpr (AXPBY) {
                         if (whole) {
-                            scale_into<V>(val, y, sc);
+                            scale_into<V, true>(val, y, sc);
                         } else {
 #pragma unroll
                             for (int i = 0; i < V; ++i) val[i] *= sc.alpha;          // lands on beta * Y (prepare)
                         }
                     }
-                    if (whole) store_vec<V>(y, val); else atomic_add_vec<V>(y, val);
+                    if (RAGGED && mine.skip != 0) {
+#pragma unroll
+                        for (int i = 1; i < V; ++i) {
+                            if (i >= mine.skip) { if (whole) y[i] = val[i]; else unsafeAtomicAdd(y + i, val[i]); }
+                        }
+                    } else if (whole) {
+                        store_vec_dword_aligned<V>(y, val);
+                    } else {
+                        atomic_add_vec<V>(y, val);
+                    }
                 }
             }
         }

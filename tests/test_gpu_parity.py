@@ -746,3 +746,30 @@ def test_matrix_that_is_already_on_the_device(dg):
         yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
         ok, worst = oracle.within_bound(Y.cpu().numpy(), yref, bnd, TOL)
         assert ok, (N, worst)
+
+
+# ------------------------------------------------------------------ widths that are no multiple of the vector width
+@pytest.mark.parametrize("N", [3, 5, 6, 7, 9, 41, 47, 63, 65, 66, 67, 129, 130, 257, 300])
+def test_widths_that_are_no_multiple_of_four(dg, N):
+    """The sequential kernels give a lane four columns and let the last lane of a row re-use columns of its
+    neighbour: on a matrix with hub rows (partial sums meet through LDS slots and atomic adds) and many empty
+    rows, plain and scaled (beta != 0 reads the old Y, which the neighbour may already have replaced), and on
+    a view one float into a wider buffer (rows start at odd dword addresses)."""
+    import torch
+    A = wl.rmat_csr(scale=12, avg_degree=14, seed=N)
+    X = wl.dense_matrix(A.K, N, "normal", seed=N)
+    ref = check(dg, A, X, x_offset=1, y_offset=3)
+    yref, bnd = ref
+    Y0 = wl.dense_matrix(A.M, N, "uniform", seed=N + 1)
+    alpha, beta = -1.5, 0.75
+    want = alpha * yref + beta * Y0.astype(np.float64)
+    bound = abs(alpha) * bnd + abs(beta) * np.abs(Y0.astype(np.float64))
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    for algo in (0, 1, 2, 3, dg.AUTO):
+        print(f"[case] ragged axpby N={N} algo={algo}", flush=True)
+        dY = torch.from_numpy(Y0).cuda()
+        dg.dgsp_spmm_csr_axpby(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, alpha, beta, algo, dA.features)
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), want, bound, 2e-5)
+        assert ok, f"algo {algo}: worst |err|/bound = {worst:.3e}"
