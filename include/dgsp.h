@@ -131,11 +131,12 @@ typedef struct {
  *             any row-length distribution).
  *   stream    hipStream_t as void*, NULL = default stream.
  *
- * Every algo accepts every N >= 1 and any (float) alignment of X and Y.  The
- * parallel-reduction kernels use vector loads of width v in {4, 2} when N and
- * the leading dimensions are multiples of v and X, Y are 4v-byte aligned, and
- * one pass per v columns; the sequential-reduction kernels give a lane four
- * columns for every N >= 4 at any alignment (two for N = 2, 3).
+ * Every algo accepts every N >= 1 and any (float) alignment of X and Y; no
+ * vector path depends on alignment or on the leading dimensions.  The
+ * parallel-reduction kernels load v dense values per entry, v the widest of
+ * 4, 3, 2, 1 that divides N (8 as two accesses in DGSP_NB_PR when 8 divides
+ * N), and make one pass over A per v columns; the sequential-reduction kernels
+ * give a lane four columns for every N >= 4 except 6.
  * M == 0 or N == 0: returns DGSP_OK without launching.  The number of stored
  * entries is read on the device from rowptr[M]; the call never synchronises.
  */

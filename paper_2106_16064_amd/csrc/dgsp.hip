@@ -92,6 +92,13 @@ inline int vector_width(const Problem& p) {
     return v;
 }
 
+// Dense columns per lane and pass of the parallel-reduction kernels: the widest of 4, 3, 2 that divides N (one
+// dwordx4 / x3 / x2 access, taken at any dword address, so alignment and leading dimensions do not matter).
+inline int pr_vector_width(const Problem& p) {
+    if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return 1;
+    return p.N % 4 == 0 ? 4 : p.N % 3 == 0 ? 3 : p.N % 2 == 0 ? 2 : 1;
+}
+
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
     do {                                                                                      \
         hipLaunchKernelGGL(kernel, grid, dim3(kBlock), 0, p.stream, __VA_ARGS__);             \
@@ -148,8 +155,9 @@ int launch_rs_pr_v(const Problem& p) {
 
 int launch_rs_pr(const Problem& p) {
     const bool xb = x_fits_descriptor(p);
-    switch (vector_width(p)) {
+    switch (pr_vector_width(p)) {
         case 4: return xb ? launch_rs_pr_v<4, true>(p) : launch_rs_pr_v<4, false>(p);
+        case 3: return xb ? launch_rs_pr_v<3, true>(p) : launch_rs_pr_v<3, false>(p);
         case 2: return xb ? launch_rs_pr_v<2, true>(p) : launch_rs_pr_v<2, false>(p);
         default: return xb ? launch_rs_pr_v<1, true>(p) : launch_rs_pr_v<1, false>(p);
     }
@@ -197,7 +205,11 @@ inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 
 struct SrShape { int v; bool ragged; };
 inline SrShape sr_shape(const Problem& p) {
     if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return {1, false};
-    const int v = p.N >= 4 ? 4 : p.N >= 2 ? 2 : 1;
+    // N = 3 and N = 6 keep the widest width that divides them: so few columns do not repay the extra stores
+    // of the shared lane (measured: +6 % at N = 6, +7 ... +17 % at N = 3 with it; N = 5 gains 13 %, N = 7 is even)
+    if (p.N == 3) return {1, false};
+    if (p.N == 6 || p.N == 2) return {2, false};
+    const int v = p.N >= 4 ? 4 : 1;
     return {v, p.N % v != 0};
 }
 // dense-row loads in flight per lane (see banded())
@@ -335,10 +347,11 @@ int launch_nb_pr_v(const Problem& p) {
 
 int launch_nb_pr(const Problem& p) {
     // eight dense columns per lane (two dwordx4 accesses) when N allows: one pass over A instead of two
-    if (vector_width(p) == 4 && p.N % 8 == 0 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
+    if (pr_vector_width(p) == 4 && p.N % 8 == 0)
         return launch_nb_pr_v<8, 1>(p);
-    switch (vector_width(p)) {
+    switch (pr_vector_width(p)) {
         case 4: return launch_nb_pr_v<4, 2>(p);
+        case 3: return launch_nb_pr_v<3, 2>(p);
         case 2: return launch_nb_pr_v<2, 2>(p);
         default: return launch_nb_pr_v<1, 2>(p);
     }

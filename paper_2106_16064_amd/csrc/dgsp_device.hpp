@@ -54,7 +54,7 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned nb) {
 }
 
 // ---------------------------------------------------------------------------
-// loads / stores of V consecutive floats (V in {1, 2, 4})
+// loads / stores of V consecutive floats (V in {1, 2, 3, 4, 8}; V-float alignment assumed for 2, 4, 8)
 // ---------------------------------------------------------------------------
 
 template <int V>
@@ -69,7 +69,10 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&x)
     } else if constexpr (V == 2) {
         const float2 t = *reinterpret_cast<const float2*>(p);
         x[0] = t.x; x[1] = t.y;
+    } else if constexpr (V == 3) {
+        __builtin_memcpy(&x[0], p, 12);
     } else {
+        static_assert(V == 1, "unsupported width");
         x[0] = *p;
     }
 }
@@ -83,22 +86,23 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x
         *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
     } else if constexpr (V == 2) {
         *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
+    } else if constexpr (V == 3) {
+        __builtin_memcpy(p, &x[0], 12);
     } else {
+        static_assert(V == 1, "unsupported width");
         *p = x[0];
     }
 }
 
 // The same for global addresses that are only known to be dword aligned (rows of a matrix whose leading
-// dimension is not a multiple of V): still one dwordx2 / dwordx4 access, which the memory pipeline takes at
-// any dword address; the compiler is merely told not to assume more.
+// dimension is not a multiple of V): still one dwordx2 / x3 / x4 access (two for V = 8), which the memory
+// pipeline takes at any dword address; the compiler is merely told not to assume more.
 template <int V>
 __device__ __forceinline__ void load_vec_dword_aligned(const float* __restrict__ p, float (&x)[V]) {
-    static_assert(V == 1 || V == 2 || V == 4, "one access");
     __builtin_memcpy(&x[0], p, sizeof(float) * V);
 }
 template <int V>
 __device__ __forceinline__ void store_vec_dword_aligned(float* __restrict__ p, const float (&x)[V]) {
-    static_assert(V == 1 || V == 2 || V == 4, "one access");
     __builtin_memcpy(p, &x[0], sizeof(float) * V);
 }
 
@@ -160,7 +164,14 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
         typedef unsigned u2 __attribute__((ext_vector_type(2)));
         const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, 0));
         x[0] = t.x; x[1] = t.y;
+    } else if constexpr (V == 3) {
+        typedef float f3 __attribute__((ext_vector_type(3)));
+        // the whole vector changes type at once: taking the integer elements one by one and casting each made
+        // the compiler load a single dword and copy it into all three
+        const f3 t = __builtin_bit_cast(f3, __builtin_amdgcn_raw_buffer_load_b96(rsrc, byte_offset, 0, 0));
+        x[0] = t.x; x[1] = t.y; x[2] = t.z;
     } else {
+        static_assert(V == 1, "unsupported width");
         x[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, byte_offset, 0, 0));
     }
 }
@@ -186,7 +197,13 @@ __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, un
         typedef unsigned u2 __attribute__((ext_vector_type(2)));
         const f2 t = {x[0], x[1]};
         __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2, t), rsrc, byte_offset, 0, AUX);
+    } else if constexpr (V == 3) {
+        typedef float f3 __attribute__((ext_vector_type(3)));
+        typedef unsigned u3 __attribute__((ext_vector_type(3)));
+        const f3 t = {x[0], x[1], x[2]};
+        __builtin_amdgcn_raw_buffer_store_b96(__builtin_bit_cast(u3, t), rsrc, byte_offset, 0, AUX);
     } else {
+        static_assert(V == 1, "unsupported width");
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x[0]), rsrc, byte_offset, 0, AUX);
     }
 }

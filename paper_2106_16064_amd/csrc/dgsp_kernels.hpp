@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
         if constexpr (XBUF) {
             buffer_load_vec<V>(rx, ok ? c * (unsigned)ldx * 4u + (unsigned)n0 * 4u : kOutOfRange, x);
         } else {
-            load_vec<V>(X + (size_t)c * ldx + n0, x);                      // c is 0 when switched off: a valid row
+            load_vec_dword_aligned<V>(X + (size_t)c * ldx + n0, x);                      // c is 0 when switched off: a valid row
 #pragma unroll
             for (int i = 0; i < V; ++i) x[i] = ok ? x[i] : 0.0f;
         }
@@ -135,8 +135,8 @@ __global__ __launch_bounds__(kBlock) void rs_pr_kernel(int M, long long K, int N
                 const unsigned long long row = row0 + (unsigned)(u * rows_per_wave + g);
                 if (row < (unsigned long long)M && gl == G - 1) {
                     float* y = Y + (size_t)row * ldy + n0;
-                    if constexpr (AXPBY) scale_into<V>(acc[u], y, sc);
-                    store_vec<V>(y, acc[u]);
+                    if constexpr (AXPBY) scale_into<V, true>(acc[u], y, sc);
+                    store_vec_dword_aligned<V>(y, acc[u]);
                 }
             }
         }
@@ -527,8 +527,8 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
             float out[V];
 #pragma unroll
             for (int i = 0; i < V; ++i) out[i] = 0.0f;
-            if constexpr (AXPBY) scale_into<V>(out, y, sc);
-            store_vec<V>(y, out);
+            if constexpr (AXPBY) scale_into<V, true>(out, y, sc);
+            store_vec_dword_aligned<V>(y, out);
         }
         continue;
     }
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
                 buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e]);
         } else {
 #pragma unroll
-            for (int e = 0; e < E; ++e) load_vec<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * ldx + n0, x[e]);
+            for (int e = 0; e < E; ++e) load_vec_dword_aligned<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * ldx + n0, x[e]);
         }
         {
             const bool more = d1 - ds > (unsigned)W;       // past the chunk's last tile the loads are switched off

@@ -154,7 +154,9 @@ def test_tall_skinny_and_wide(dg):
 
 
 @pytest.mark.parametrize("N,xoff,yoff", [(4, 1, 0), (4, 0, 1), (4, 2, 2), (8, 3, 1), (2, 1, 1), (64, 2, 0)])
-def test_unaligned_buffers_take_narrower_vector_paths(dg, N, xoff, yoff):
+def test_buffers_at_odd_dword_addresses(dg, N, xoff, yoff):
+    """X and Y a few floats into their allocations: the multi-dword accesses of every kernel then start at
+    addresses that are multiples of 4 bytes only; nothing next to Y may change."""
     A = wl.poisson_csr(2000, 2000, 12.0, seed=5)
     check(dg, A, wl.dense_matrix(A.K, N, "normal", seed=5), x_offset=xoff, y_offset=yoff)
 
