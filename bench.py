@@ -26,6 +26,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -354,8 +355,10 @@ def run_sweep(args):
                 del rot
             print(f"[sweep] {A.name} done", file=sys.stderr, flush=True)
     losses.sort()
+    geomean = math.exp(sum(math.log1p(l) for l in losses) / len(losses)) - 1.0      # geometric mean of t_selected / t_best, minus 1
     print(json.dumps({"suite": "sweep", "cells": len(losses), "mean_loss": sum(losses) / len(losses),
-                      "median_loss": losses[len(losses) // 2], "max_loss": losses[-1], "file": path}))
+                      "geomean_loss": geomean, "median_loss": losses[len(losses) // 2], "max_loss": losses[-1],
+                      "file": path}))
     return 0
 
 
@@ -554,6 +557,8 @@ def run_fit(args):
         "thresholds": dict(zip(THRESHOLD_NAMES, best)),
         "mean_loss_fit_seed0": loss(fit, best)[0], "mean_loss_heldout_seed1": loss(test, best)[0],
         "mean_loss_sweep_all": loss(rows, best)[0], "max_loss_sweep_all": loss(rows, best)[1],
+        "geomean_loss_sweep_all": math.exp(sum(math.log(r["ms"][choose(r, best)] / min(r["ms"].values())) for r in rows)
+                                           / len(rows)) - 1.0,
         "mean_loss_size_cells": loss(big, best)[0], "max_loss_size_cells": loss(big, best)[1],
         "added_rules_off": {"no_short_row_rule": variant(short_avg_row_max=0.0, short_max_row_max=0),
                             "no_size_guard": variant(pr_nnz_max=inf),
