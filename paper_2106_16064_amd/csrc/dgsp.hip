@@ -246,15 +246,18 @@ int launch_rs_sr_v(const Problem& p) {
 
 template <int V>
 int launch_rs_sr_direct_v(const Problem& p) {
-    const int logG = sr_lanes_log2(p.N, V);
-    const long long cols_per_block = (long long)V << logG;
-    const unsigned col_blocks = (unsigned)((p.N + cols_per_block - 1) / cols_per_block);
+    // the same column blocks as the kernel it is compared with
+    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= g_thresholds.sr_cv_min;
+    const SrColumns cols = sr_columns(p.N, V, even_rows && p.N >= 128);
+    const int logG = cols.logG;
+    const unsigned col_blocks = cols.blocks;
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int rows_per_wave = kWave >> logG;
     const long long groups = ((long long)p.M + rows_per_wave - 1) / rows_per_wave;
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
-    DGSP_LAUNCH((rs_sr_direct_kernel<V>), grid, p.M, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
+    DGSP_LAUNCH((rs_sr_direct_kernel<V>), grid, p.M, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG,
+                cols.cols_per_block);
     return DGSP_OK;
 }
 

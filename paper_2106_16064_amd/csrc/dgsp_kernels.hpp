@@ -275,14 +275,15 @@ __global__ __launch_bounds__(kBlock) void rs_sr_direct_kernel(int M, int N, int 
                                                                const int* __restrict__ colidx,
                                                                const float* __restrict__ vals,
                                                                const float* __restrict__ X, float* __restrict__ Y,
-                                                               int logG) {
+                                                               int logG, int cols_per_block) {
     const int lane = lane_id();
     const int G = 1 << logG;
     const int gl = lane & (G - 1);
     const int g = lane >> logG;
     const int rows_per_wave = kWave >> logG;
-    const long long n = ((long long)blockIdx.y * G + gl) * V;
-    const bool col_ok = n < N;
+    const LaneColumns mine = lane_columns<V, false>(blockIdx.y, cols_per_block, gl, N);
+    const long long n = mine.first;
+    const bool col_ok = mine.any;
     const unsigned nwaves = gridDim.x * kWavesPerBlock;
     const unsigned gw = xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
     const unsigned ngroups = ((unsigned)M + rows_per_wave - 1) / rows_per_wave;
