@@ -280,7 +280,7 @@ int launch_rs_sr(const Problem& p) {
     const SrShape shape = sr_shape(p);
     switch (shape.v) {
         case 4: return shape.ragged ? launch_rs_sr_pick<4, true>(p) : launch_rs_sr_pick<4, false>(p);
-        case 2: return shape.ragged ? launch_rs_sr_pick<2, true>(p) : launch_rs_sr_pick<2, false>(p);
+        case 2: return launch_rs_sr_pick<2, false>(p);
         default: return launch_rs_sr_pick<1, false>(p);
     }
 }
@@ -402,7 +402,7 @@ int launch_nb_sr(const Problem& p) {
     const SrShape shape = sr_shape(p);
     switch (shape.v) {
         case 4: return shape.ragged ? launch_nb_sr_pick<4, true>(p) : launch_nb_sr_pick<4, false>(p);
-        case 2: return shape.ragged ? launch_nb_sr_pick<2, true>(p) : launch_nb_sr_pick<2, false>(p);
+        case 2: return launch_nb_sr_pick<2, false>(p);
         default: return launch_nb_sr_pick<1, false>(p);
     }
 }

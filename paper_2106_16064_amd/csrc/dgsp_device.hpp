@@ -271,18 +271,26 @@ __device__ __forceinline__ LaneColumns lane_columns(unsigned block, int cols_per
 }
 
 // Stores a lane's V results at byte_offset (kOutOfRange: nothing), leaving out its first `skip`.
+// `tail` = N % V (wave-uniform): the lane with skip != 0 owns exactly its last `tail` values, so they leave in
+// one more store of that width, issued by the whole wave and switched off everywhere else.
 template <int V, bool RAGGED, int AUX = 0>
 __device__ __forceinline__ void buffer_store_columns(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V],
-                                                     int skip) {
+                                                     int skip, int tail) {
     if constexpr (!RAGGED) {
         buffer_store_vec<V, AUX>(rsrc, byte_offset, x);
     } else {
+        static_assert(V == 4, "the shared lane exists at four columns per lane only");
         buffer_store_vec<V, AUX>(rsrc, skip == 0 ? byte_offset : kOutOfRange, x);
-#pragma unroll
-        for (int i = 1; i < V; ++i) {                       // at most one lane of a group takes this part
-            const float one[1] = {x[i]};
-            const bool on = skip != 0 && i >= skip && byte_offset != kOutOfRange;
-            buffer_store_vec<1, AUX>(rsrc, on ? byte_offset + 4u * (unsigned)i : kOutOfRange, one);
+        const bool on = skip != 0 && byte_offset != kOutOfRange;
+        if (tail == 1) {
+            const float t[1] = {x[3]};
+            buffer_store_vec<1, AUX>(rsrc, on ? byte_offset + 12u : kOutOfRange, t);
+        } else if (tail == 2) {
+            const float t[2] = {x[2], x[3]};
+            buffer_store_vec<2, AUX>(rsrc, on ? byte_offset + 8u : kOutOfRange, t);
+        } else {
+            const float t[3] = {x[1], x[2], x[3]};
+            buffer_store_vec<3, AUX>(rsrc, on ? byte_offset + 4u : kOutOfRange, t);
         }
     }
 }

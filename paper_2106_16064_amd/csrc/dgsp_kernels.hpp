@@ -809,6 +809,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const LaneColumns mine = lane_columns<V, RAGGED>(blockIdx.y, cols_per_block, gl, N);
     const long long n = mine.first;
     const bool col_ok = mine.any;
+    const int tail = N % V;                  // columns of the lane that shares its window (RAGGED)
 
     const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
     const unsigned nnz = plan.nnz;
@@ -902,9 +903,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                         for (int i = 0; i < V; ++i) out[i] = 0.0f;
                         scale_into<V>(out, yrows, off, sc);               // beta * Y
-                        buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip);
+                        buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip, tail);
                     } else {
-                        buffer_store_columns<V, RAGGED, 2>(yrows, off, zero, mine.skip);
+                        buffer_store_columns<V, RAGGED, 2>(yrows, off, zero, mine.skip, tail);
                     }
                 }
             }
@@ -973,9 +974,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                     for (int i = 0; i < V; ++i) out[i] = acc[i];
                     scale_into<V>(out, yrows, off, sc);
-                    buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip);
+                    buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip, tail);
                 } else {
-                    buffer_store_columns<V, RAGGED, 2>(yrows, off, acc, mine.skip);
+                    buffer_store_columns<V, RAGGED, 2>(yrows, off, acc, mine.skip, tail);
                 }
                 if (closing) {
                     if (!direct) to_slot(true);
