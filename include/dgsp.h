@@ -68,9 +68,10 @@ typedef struct {
     double avg_row, stdv_row, cv_row;
     int64_t max_row, min_row;
     double col_span; /* mean over non-empty rows of (largest - smallest column + 1) / K; 0 = unknown.
-                        Not part of the paper's rules: it does not change which kernel runs, only how
-                        many dense-row loads the sequential kernels keep in flight (a banded matrix,
-                        col_span <= 0.05, re-uses rows of X between neighbouring rows and wants more). */
+                        Not part of the paper's rules.  It tells the sequential kernels how many
+                        dense-row loads to keep in flight (a banded matrix, col_span <= 0.05, re-uses
+                        rows of X between neighbouring rows and wants more), and the added
+                        large-dense-operand rule of the selector looks at it (see below). */
 } dgsp_features_t;
 
 /* Selector thresholds (Section 2.2 says they are set empirically and prints no
@@ -99,7 +100,17 @@ typedef struct {
  *              sequential.  When no row is long, one lane group per row keeps the
  *              whole wave busy for max_row steps with no cross-lane step and no
  *              long-row tail; it beat the other three kernels on every such
- *              matrix measured.  Set short_avg_row_max to 0 to switch it off.  */
+ *              matrix measured.  Set short_avg_row_max to 0 to switch it off.
+ *   large dense operand (an addition, checked second, on the parallel side
+ *              N <= n_parallel_max only): K * N * 4 >= big_x_bytes_min AND
+ *              cv_row <= big_x_cv_max AND avg_row <= big_x_avg_row_max AND
+ *              col_span >= 0.5 -> row-split sequential.  When X no longer fits
+ *              one XCD's 4 MB L2, rows of about equal length whose ascending
+ *              columns spread over most of K are swept in step by the lanes of
+ *              a wave, one row per lane, so the part of X in use at a time stays
+ *              small; the parallel kernels spread one row over the lanes and touch
+ *              all of X at once (measured 10-80 % slower there).  Needs col_span;
+ *              big_x_bytes_min 0 switches it off.  */
 typedef struct {
     int64_t n_parallel_max;
     double pr_avg_row_min;
@@ -110,6 +121,9 @@ typedef struct {
     double short_avg_row_max;
     int64_t short_max_row_max;
     int64_t wide_parallel_n;
+    int64_t big_x_bytes_min;
+    double big_x_cv_max;
+    double big_x_avg_row_max;
 } dgsp_thresholds_t;
 
 /*

@@ -420,6 +420,9 @@ dgsp_thresholds_t g_thresholds = {
     /* short_avg_row_max */ 20.0,
     /* short_max_row_max */ 64,
     /* wide_parallel_n   */ 8,
+    /* big_x_bytes_min   */ 6000000,
+    /* big_x_cv_max      */ 0.2,
+    /* big_x_avg_row_max */ 64.0,
 };
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
@@ -536,6 +539,10 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     // all rows short: one lane group per row keeps a wave busy with no cross-lane step and no idle tail
     if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
     if (N <= t.n_parallel_max) {
+        // X beyond one L2, rows alike and spread over all columns: one row per lane sweeps X in step
+        if (t.big_x_bytes_min > 0 && (double)f->K * (double)N * 4.0 >= (double)t.big_x_bytes_min &&
+            f->cv_row <= t.big_x_cv_max && f->avg_row <= t.big_x_avg_row_max && f->col_span >= 0.5)
+            return DGSP_RS_SR;
         // parallel reduction: long rows keep a row's lanes busy, short rows idle them
         const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max && f->nnz < t.pr_nnz_max;
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;

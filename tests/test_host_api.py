@@ -73,7 +73,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0, 0)      # the paper's rule verbatim (no added guards)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0, 0, 0, 0.0, 0.0)   # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -116,6 +116,20 @@ def test_selection_rules_follow_the_decision_tree():
         assert dg.dgsp_select_algo(feat(64, 1.5), 16) == dg.NB_SR
         assert dg.dgsp_select_algo(feat(64, 1.5), 7) == dg.NB_SR
         assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_SR           # even rows: row-split as before
+        t.big_x_bytes_min, t.big_x_cv_max, t.big_x_avg_row_max = 6_000_000, 0.2, 64.0     # the added large-X rule
+        t.pr_nnz_max = 2**62
+        dg.dgsp_set_thresholds(t)
+        f = feat(30, 0.1, M=1 << 20); f.col_span = 0.9                     # K * 4 * 4 = 16 MB, rows alike, columns spread
+        assert dg.dgsp_select_algo(f, 4) == dg.RS_SR and dg.dgsp_select_algo(f, 2) == dg.RS_SR
+        assert dg.dgsp_select_algo(f, 1) == dg.NB_PR                       # 4 MB: X still fits an L2
+        f.col_span = 0.01
+        assert dg.dgsp_select_algo(f, 4) == dg.NB_PR                       # banded: neighbours share X anyway
+        f.col_span = 0.0
+        assert dg.dgsp_select_algo(f, 4) == dg.NB_PR                       # span unknown: the rule stays out
+        f = feat(30, 0.6, M=1 << 20); f.col_span = 0.9
+        assert dg.dgsp_select_algo(f, 4) == dg.NB_PR                       # uneven rows
+        f = feat(100, 0.1, M=1 << 20); f.col_span = 0.9
+        assert dg.dgsp_select_algo(f, 4) == dg.RS_PR                       # long rows: the tree's parallel side
         L = dg.lib()
         assert L.dgsp_select_algo(None, 4) == dg.AUTO
         assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
