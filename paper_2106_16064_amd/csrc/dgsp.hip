@@ -198,10 +198,10 @@ inline SrColumns sr_columns(long long N, int V, bool narrow) {
 // known to be banded (neighbouring rows then share their rows of X and mostly hit in cache).
 inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 0.05; }
 
-// The sequential kernels give a lane four dense columns whenever a row has four (two when it has two or
-// three): the memory pipeline takes dwordx2 / dwordx4 accesses at any dword address, so neither the alignment
-// of X and Y nor their leading dimensions restrict the width.  When N is not a multiple of it the last lane of a
-// row takes the row's last columns and leaves out those it shares with its neighbour (RAGGED).
+// The sequential kernels give a lane four dense columns whenever a row has four: the memory pipeline takes
+// dwordx2 / dwordx4 accesses at any dword address, so neither the alignment of X and Y nor their leading
+// dimensions restrict the width.  When N is not a multiple of four the last lane of a row takes the row's last
+// four columns and leaves out those it shares with its neighbour (RAGGED).
 struct SrShape { int v; bool ragged; };
 inline SrShape sr_shape(const Problem& p) {
     if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return {1, false};
