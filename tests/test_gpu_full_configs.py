@@ -170,3 +170,43 @@ def test_more_than_two_to_the_thirty_entries(dg):
             Y = dY[torch.from_numpy(sample).cuda()].cpu().numpy()
             ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
             assert ok, f"{NAMES[algo]} N={N}: worst |err|/bound {worst:.3e}"
+
+
+# ------------------------------------------------------------------ dense operands beyond 4 GB
+def test_dense_operands_beyond_four_gigabytes(dg, rmat20):
+    """X and Y as column slices of 2^20 x 1100 buffers (4.6 GB each): byte offsets into them pass 2^32, so the
+    kernels leave their 32-bit descriptor addressing for X and address Y rows with 64-bit arithmetic.  Widths 1, 4,
+    8 and 5 (the shared-lane path); the balanced kernels on the R-MAT matrix, all four on a small Poisson matrix
+    whose columns span all of K.  The scaled form does not exist for such an X and must say so."""
+    import torch
+    dev = torch.device("cuda:0")
+    K = rmat20.K
+    ld = 1100
+    bigX = torch.empty((K, ld), dtype=torch.float32, device=dev)
+    bigY = torch.empty((rmat20.M, ld), dtype=torch.float32, device=dev)
+    assert bigX.numel() * 4 > (1 << 32)
+    small = wl.csr_from_lens(np.random.default_rng(3).poisson(12.0, size=20000), K, seed=4, name="poisson12_wideK")
+    cases = [(rmat20, (-1, 3, 2)), (small, (-1, 0, 1, 2, 3))]
+    for N in (1, 4, 8, 5):
+        x0, y0 = ld - N - 3, ld - N
+        X = wl.dense_matrix(K, N, "uniform", seed=70 + N)
+        bigX[:, x0:x0 + N] = torch.from_numpy(X).to(dev)
+        for A, algos in cases:
+            yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+            dA = dg.DeviceCsr(A)
+            for algo in algos:
+                print(f"[case] beyond 4 GB {A.name} N={N} algo={NAMES[algo]}", flush=True)
+                bigY[:A.M, y0 - 2:] = float("nan")
+                dg.dgsp_spmm_csr_ld(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, bigX[:, x0:x0 + N],
+                                    bigY[:A.M, y0:y0 + N], algo, dA.features)
+                torch.cuda.synchronize()
+                out = bigY[:A.M, y0 - 2:].cpu().numpy()
+                assert np.isnan(out[:, :2]).all(), "wrote left of the slice"
+                Y = out[:, 2:]
+                assert not np.isnan(Y).any()
+                ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+                assert ok, f"{NAMES[algo]} on {A.name} N={N}: worst |err|/bound {worst:.3e}"
+    dA = dg.DeviceCsr(small)
+    with pytest.raises(dg.DgspError):
+        dg.dgsp_spmm_csr_axpby(small.M, small.K, 4, small.nnz, dA.rowptr, dA.colidx, dA.vals, bigX[:, 0:4],
+                               bigY[:small.M, 0:4], 2.0, 0.0, dg.NB_SR, dA.features)
