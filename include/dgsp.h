@@ -55,7 +55,9 @@ typedef enum {
     DGSP_OK = 0,
     DGSP_ERR_INVALID_ARG = 1, /* negative extent, NULL pointer with non-zero extent,
                                  unknown algo, extent beyond the int32 index range   */
-    DGSP_ERR_UNSUPPORTED = 2, /* reserved                                            */
+    DGSP_ERR_UNSUPPORTED = 2, /* valid arguments outside a stated limit of the kernel asked
+                                 for (ldy beyond 2^20 in the balanced kernels; a measurement
+                                 switch the kernel does not offer)                   */
     DGSP_ERR_LAUNCH = 3       /* the HIP runtime refused a launch                    */
 } dgsp_status_t;
 
@@ -286,7 +288,7 @@ int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz,
  * With beta == 0 the old contents of Y are not read (they may be anything,
  * NaN included).  Rows of A without entries give beta * Y.  Rows whose partial
  * sums meet through atomic adds are first multiplied by beta by the prepare
- * launch.  Available for X below 4 GB, else DGSP_ERR_UNSUPPORTED.  Other
+ * launch.  Other
  * arguments, vector-width rule and algo == DGSP_AUTO as in dgsp_spmm_csr_ld.
  */
 int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,

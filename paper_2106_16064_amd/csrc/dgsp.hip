@@ -141,13 +141,9 @@ int launch_rs_pr_v(const Problem& p) {
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap));
     if (p.scaled) {
-        if constexpr (XBUF) {
-            DGSP_LAUNCH((rs_pr_kernel<V, true, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
-                        p.Y, logG, Scaling{p.alpha, p.beta});
-            return DGSP_OK;
-        } else {
-            return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
-        }
+        DGSP_LAUNCH((rs_pr_kernel<V, XBUF, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
+                    p.Y, logG, Scaling{p.alpha, p.beta});
+        return DGSP_OK;
     }
     DGSP_LAUNCH((rs_pr_kernel<V, XBUF>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y, logG);
     return DGSP_OK;
@@ -231,13 +227,9 @@ int launch_rs_sr_v(const Problem& p) {
     const long long cap = (long long)device_info().cus * kBlocksPerCu * 8;
     const dim3 grid(clamp_blocks((groups + kWavesPerBlock - 1) / kWavesPerBlock, cap), col_blocks);
     if (p.scaled) {
-        if constexpr (XBUF) {
-            DGSP_LAUNCH((rs_sr_kernel<V, true, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals,
-                        p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
-            return DGSP_OK;
-        } else {
-            return DGSP_ERR_UNSUPPORTED;
-        }
+        DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals,
+                    p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
+        return DGSP_OK;
     }
     DGSP_LAUNCH((rs_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
                 p.Y, logG, cols.cols_per_block);
@@ -373,15 +365,13 @@ int launch_nb_sr_v(const Problem& p) {
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
     if (p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
-    if (p.scaled && !XBUF) return DGSP_ERR_UNSUPPORTED;      // the scaled variants exist for X below 4 GB only
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
         if (p.scaled) {
-            if constexpr (XBUF)
-                DGSP_LAUNCH((nb_sr_kernel<V, true, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
-                            p.vals, p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
+            DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
+                        p.vals, p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
         } else {
             DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
                         logG, cols.cols_per_block);

@@ -177,7 +177,7 @@ def test_dense_operands_beyond_four_gigabytes(dg, rmat20):
     """X and Y as column slices of 2^20 x 1100 buffers (4.6 GB each): byte offsets into them pass 2^32, so the
     kernels leave their 32-bit descriptor addressing for X and address Y rows with 64-bit arithmetic.  Widths 1, 4,
     8 and 5 (the shared-lane path); the balanced kernels on the R-MAT matrix, all four on a small Poisson matrix
-    whose columns span all of K.  The scaled form does not exist for such an X and must say so."""
+    whose columns span all of K, the latter also in the scaled form."""
     import torch
     dev = torch.device("cuda:0")
     K = rmat20.K
@@ -206,7 +206,19 @@ def test_dense_operands_beyond_four_gigabytes(dg, rmat20):
                 assert not np.isnan(Y).any()
                 ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
                 assert ok, f"{NAMES[algo]} on {A.name} N={N}: worst |err|/bound {worst:.3e}"
+    # the scaled form on the same operands (N = 5 is still in place in bigX)
+    N, alpha, beta = 5, 2.0, -0.5
+    x0, y0 = ld - N - 3, ld - N
+    yref, bnd = oracle.spmm_ref(small.M, small.K, N, small.rowptr, small.colidx, small.vals, X)
+    Y0 = wl.dense_matrix(small.M, N, "uniform", seed=9)
+    want = alpha * yref + beta * Y0.astype(np.float64)
+    bound = abs(alpha) * bnd + abs(beta) * np.abs(Y0.astype(np.float64))
     dA = dg.DeviceCsr(small)
-    with pytest.raises(dg.DgspError):
-        dg.dgsp_spmm_csr_axpby(small.M, small.K, 4, small.nnz, dA.rowptr, dA.colidx, dA.vals, bigX[:, 0:4],
-                               bigY[:small.M, 0:4], 2.0, 0.0, dg.NB_SR, dA.features)
+    for algo in (-1, 0, 1, 2, 3):
+        print(f"[case] beyond 4 GB scaled N={N} algo={NAMES[algo]}", flush=True)
+        bigY[:small.M, y0:y0 + N] = torch.from_numpy(Y0).to(dev)
+        dg.dgsp_spmm_csr_axpby(small.M, small.K, N, small.nnz, dA.rowptr, dA.colidx, dA.vals, bigX[:, x0:x0 + N],
+                               bigY[:small.M, y0:y0 + N], alpha, beta, algo, dA.features)
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_bound(bigY[:small.M, y0:y0 + N].cpu().numpy(), want, bound, 2e-5)
+        assert ok, f"scaled {NAMES[algo]}: worst |err|/bound {worst:.3e}"
