@@ -784,6 +784,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int W = kNbSrTile;
+    constexpr int kStoreAux = V == 4 ? 2 : 0;           // results leave non-temporal when rows are 16 bytes or more per lane
     constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
     __shared__ int s_col[kWavesPerBlock][W];
     __shared__ float s_val[kWavesPerBlock][W];
@@ -881,8 +882,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
             (void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left, kBufferFlags);
 
         // rows without entries get their zeros here, all groups together (group g: local rows g, g + groups, ...),
-        // so that the walk below meets a store only where a row with entries ends.  Results are stored
-        // non-temporal here and in the walk: nobody reads them again, the L2 is for rows of X (1-2 % measured).
+        // so that the walk below meets a store only where a row with entries ends.  With four columns per lane
+        // results are stored non-temporal here and in the walk: nobody reads them again, the L2 is for rows of X
+        // (1-4 % measured at N >= 8; at N = 1, 2 the narrow stores were 4-8 % slower that way).
         {
             float zero[V];
 #pragma unroll
@@ -903,9 +905,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                         for (int i = 0; i < V; ++i) out[i] = 0.0f;
                         scale_into<V>(out, yrows, off, sc);               // beta * Y
-                        buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip, tail);
+                        buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, out, mine.skip, tail);
                     } else {
-                        buffer_store_columns<V, RAGGED, 2>(yrows, off, zero, mine.skip, tail);
+                        buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, zero, mine.skip, tail);
                     }
                 }
             }
@@ -974,9 +976,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                     for (int i = 0; i < V; ++i) out[i] = acc[i];
                     scale_into<V>(out, yrows, off, sc);
-                    buffer_store_columns<V, RAGGED, 2>(yrows, off, out, mine.skip, tail);
+                    buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, out, mine.skip, tail);
                 } else {
-                    buffer_store_columns<V, RAGGED, 2>(yrows, off, acc, mine.skip, tail);
+                    buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, acc, mine.skip, tail);
                 }
                 if (closing) {
                     if (!direct) to_slot(true);
