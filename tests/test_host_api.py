@@ -172,3 +172,31 @@ def test_c_example_builds_and_links_against_the_library():
     from paper_2106_16064_amd import build
     exe = build.build_c_example(verbose=False)
     assert exe.exists() and exe.stat().st_size > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
+
+
+def test_default_thresholds_and_their_effect_on_benchmark_shapes():
+    """The shipped rules on the statistics of the benchmark's matrices (computed here from the generators):
+    R-MAT -> balanced kernels, stencil -> balanced parallel up to N = 4 and row-split sequential at 8,
+    equal rows of random columns -> row-split sequential once X outgrows an L2."""
+    t = dg.dgsp_get_thresholds()
+    assert (t.n_parallel_max, t.wide_parallel_n, t.big_x_bytes_min) == (4, 8, 6_000_000)
+    R = wl.rmat_csr(14, 16, seed=0)
+    f = dg.dgsp_features_from_csr_host(R.M, R.K, R.rowptr, R.colidx)
+    assert [dg.dgsp_select_algo(f, n) for n in (1, 4, 8, 32)] == [dg.NB_PR, dg.NB_PR, dg.NB_PR, dg.NB_SR]
+    S = wl.stencil27_csr(24)
+    f = dg.dgsp_features_from_csr_host(S.M, S.K, S.rowptr, S.colidx)
+    f.nnz = 55_742_968                       # as large as the benchmark's grid: beyond the single-launch size guard
+    assert [dg.dgsp_select_algo(f, n) for n in (1, 2, 4, 8)] == [dg.NB_PR, dg.NB_PR, dg.NB_PR, dg.RS_SR]
+    E = wl.sweep_csr(1 << 12, 27, "fixed", 0)
+    f = dg.dgsp_features_from_csr_host(E.M, E.K, E.rowptr, E.colidx)
+    assert f.cv_row == 0.0 and f.col_span > 0.8
+    assert dg.dgsp_select_algo(f, 4) == dg.NB_PR        # 4096 columns: X is 64 KB
+    f.K = 1 << 20                                       # the same rows over 2^20 columns: X is 16 MB at N = 4
+    assert dg.dgsp_select_algo(f, 4) == dg.RS_SR and dg.dgsp_select_algo(f, 1) == dg.NB_PR
