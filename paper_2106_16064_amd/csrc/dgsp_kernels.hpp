@@ -381,7 +381,9 @@ __global__ __launch_bounds__(kBlock) void nb_prepare_kernel(int M, int N, int ld
     if (row < M) {
         const unsigned first = (unsigned)row + (unsigned)rowptr[row];       // diagonal of the row's first item
         const unsigned last = (unsigned)row + (unsigned)rowptr[row + 1];    // diagonal of its end marker
-        if (first != last) {                                                 // an empty row is a single item
+        // An empty row is a single item.  Every chunk and tile starts at a multiple of the quantum, so a row
+        // whose items lie inside one quantum cannot be split: most rows stop here, before the divisions.
+        if (first != last && (first >> quantum_log2) != (last >> quantum_log2)) {
             const EvenSplit es((unsigned)rowptr[M] + (unsigned)M, parts, quantum_log2);
             const unsigned c1 = es.chunk_of(first), c2 = es.chunk_of(last);
             split = c1 != c2;
