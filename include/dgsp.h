@@ -152,7 +152,10 @@ typedef struct {
  * parallel-reduction kernels load v dense values per entry, v the widest of
  * 4, 3, 2, 1 that divides N (8 as two accesses in DGSP_NB_PR when 8 divides
  * N), and make one pass over A per v columns; the sequential-reduction kernels
- * give a lane four columns for every N >= 4 except 6.
+ * give a lane four columns for every N >= 4 except 6.  What the layout still
+ * decides is how many 128-byte lines a row of X spans: rows that start on
+ * line boundaries (ldx a multiple of 32) are fetched with the fewest requests
+ * (N = 31 with ldx = 32 ran 1.2-1.5x faster than with ldx = 31).
  * M == 0 or N == 0: returns DGSP_OK without launching.  The number of stored
  * entries is read on the device from rowptr[M]; the call never synchronises.
  */
