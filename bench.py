@@ -526,7 +526,7 @@ def run_fit(args):
             return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv and r["nnz"] < nnz_max) else "nb_pr"
         if not (r["cv_row"] > sr_cv and r["stdv"] > sr_std):
             return "rs_sr"
-        return "nb_pr" if r["N"] == wide else "nb_sr"
+        return "nb_pr" if r["N"] <= wide else "nb_sr"
 
     def loss(rs, t):
         if not rs:

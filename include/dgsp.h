@@ -91,12 +91,12 @@ typedef struct {
  *              condition is an addition: with short rows even a large cv_row
  *              leaves no row long enough to stall a wave; set sr_stdv_min to 0
  *              for the paper's rule verbatim)
- *   eight columns (an addition): N == wide_parallel_n AND the sequential side
- *              would balance -> nnz-balanced PARALLEL kernel.  That kernel reads
- *              eight dense columns per lane with two dwordx4 accesses, so N = 8
- *              is still one pass over the sparse matrix, and it beat the
- *              balanced sequential kernel by 6-18 % there.  The adaptive calls
- *              apply it only if X and Y allow 16-byte accesses.  0 switches it off.
+ *   up to eight columns (an addition): n_parallel_max < N <= wide_parallel_n
+ *              AND the sequential side would balance -> nnz-balanced PARALLEL
+ *              kernel.  That kernel reads eight dense columns per lane with two
+ *              dwordx4 accesses (for N = 5, 6, 7 the two overlap), so these N are
+ *              still one pass over the sparse matrix, and it beat the balanced
+ *              sequential kernel by 6-31 % there.  Meant for 8; 0 switches it off.
  *   short rows (an addition, checked first, at every N): avg_row <=
  *              short_avg_row_max AND max_row <= short_max_row_max -> row-split
  *              sequential.  When no row is long, one lane group per row keeps the

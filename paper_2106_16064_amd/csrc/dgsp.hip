@@ -330,7 +330,7 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
 template <int V, int KQ>
 int launch_nb_pr_v(const Problem& p) {
     constexpr unsigned tile = kWave * 4 * KQ;
-    const unsigned col_groups = (unsigned)(p.N / V);
+    const unsigned col_groups = (unsigned)((p.N + V - 1) / V);      // V = 8 also takes N = 5, 6, 7: one group
     // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
@@ -349,6 +349,9 @@ int launch_nb_pr_v(const Problem& p) {
 int launch_nb_pr(const Problem& p) {
     // eight dense columns per lane (two dwordx4 accesses) when N allows: one pass over A instead of two
     if (pr_vector_width(p) == 4 && p.N % 8 == 0)
+        return launch_nb_pr_v<8, 1>(p);
+    // N = 5, 6, 7: the same kernel with the lane's two groups of four columns overlapping - one pass
+    if (p.N >= 5 && p.N <= 7 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
         return launch_nb_pr_v<8, 1>(p);
     switch (pr_vector_width(p)) {
         case 4: return launch_nb_pr_v<4, 2>(p);
@@ -480,9 +483,6 @@ extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, co
     if (features && nnz < 0) nnz = features->nnz;
     if (algo == DGSP_AUTO && features && N >= 1) {
         algo = dgsp_select_algo(features, N);
-        if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max &&
-            (widest_vector(N, X, Y) < 4 || ldx % 4 != 0 || ldy % 4 != 0))
-            algo = DGSP_NB_SR;        // the eight-column rule needs 16-byte accesses
     }
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                Hints(features), 0, ldx, ldy);
@@ -496,9 +496,6 @@ extern "C" int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
     if (features && nnz < 0) nnz = features->nnz;
     if (algo == DGSP_AUTO && features && N >= 1) {
         algo = dgsp_select_algo(features, N);
-        if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max &&
-            (widest_vector(N, X, Y) < 4 || ldx % 4 != 0 || ldy % 4 != 0))
-            algo = DGSP_NB_SR;
     }
     const Scaling sc{alpha, beta};
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
@@ -523,7 +520,6 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
     if (features->M != M || features->nnz < 0) return DGSP_ERR_INVALID_ARG;
     int algo = (N >= 1) ? dgsp_select_algo(features, N) : DGSP_NB_PR;
     if (algo < 0) return DGSP_ERR_INVALID_ARG;
-    if (algo == DGSP_NB_PR && N > g_thresholds.n_parallel_max && widest_vector(N, X, Y) < 4) algo = DGSP_NB_SR;
     if (chosen) *chosen = algo;
     return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, Hints(features));
 }
@@ -545,8 +541,8 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     }
     // sequential reduction: balance only when stdv_row / avg_row says rows are uneven
     if (!(f->cv_row > t.sr_cv_min && f->stdv_row > t.sr_stdv_min)) return DGSP_RS_SR;
-    // eight columns fit one lane of the balanced parallel kernel: still a single pass
-    return (t.wide_parallel_n > 0 && N == t.wide_parallel_n) ? DGSP_NB_PR : DGSP_NB_SR;
+    // up to eight columns fit one lane of the balanced parallel kernel: still a single pass
+    return (N <= t.wide_parallel_n) ? DGSP_NB_PR : DGSP_NB_SR;
 }
 
 extern "C" void dgsp_get_thresholds(dgsp_thresholds_t* out) {

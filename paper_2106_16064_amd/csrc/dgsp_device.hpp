@@ -97,13 +97,26 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x
 // The same for global addresses that are only known to be dword aligned (rows of a matrix whose leading
 // dimension is not a multiple of V): still one dwordx2 / x3 / x4 access (two for V = 8), which the memory
 // pipeline takes at any dword address; the compiler is merely told not to assume more.
+// V = 8 is two groups of four; `second` says where the second group starts (4: right after the first; less:
+// the two overlap, which is how the balanced parallel kernel takes N = 5, 6, 7 in one pass - the shared
+// columns are then computed twice, identically, see second_half_own()).
 template <int V>
-__device__ __forceinline__ void load_vec_dword_aligned(const float* __restrict__ p, float (&x)[V]) {
-    __builtin_memcpy(&x[0], p, sizeof(float) * V);
+__device__ __forceinline__ void load_vec_dword_aligned(const float* __restrict__ p, float (&x)[V], int second = 4) {
+    if constexpr (V == 8) {
+        __builtin_memcpy(&x[0], p, 16);
+        __builtin_memcpy(&x[4], p + second, 16);
+    } else {
+        __builtin_memcpy(&x[0], p, sizeof(float) * V);
+    }
 }
 template <int V>
-__device__ __forceinline__ void store_vec_dword_aligned(float* __restrict__ p, const float (&x)[V]) {
-    __builtin_memcpy(p, &x[0], sizeof(float) * V);
+__device__ __forceinline__ void store_vec_dword_aligned(float* __restrict__ p, const float (&x)[V], int second = 4) {
+    if constexpr (V == 8) {
+        __builtin_memcpy(p, &x[0], 16);
+        __builtin_memcpy(p + second, &x[4], 16);      // overlapping columns hold equal values
+    } else {
+        __builtin_memcpy(p, &x[0], sizeof(float) * V);
+    }
 }
 
 // Hardware fp32 add at the L2 (global_atomic_add_f32, no return value).
@@ -111,6 +124,14 @@ template <int V>
 __device__ __forceinline__ void atomic_add_vec(float* p, const float (&x)[V]) {
 #pragma unroll
     for (int i = 0; i < V; ++i) unsafeAtomicAdd(p + i, x[i]);
+}
+// V = 8 with the second group of four at `second` <= 4: every column exactly once
+__device__ __forceinline__ void atomic_add_halves(float* p, const float (&x)[8], int second) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) unsafeAtomicAdd(p + i, x[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (second + i >= 4) unsafeAtomicAdd(p + second + i, x[4 + i]);
 }
 
 // The sparse arrays are read exactly once per call: mark the loads
@@ -146,11 +167,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* p, uns
 // Loads V consecutive floats at byte_offset; lanes whose offset is out of range get zeros and
 // cause no memory traffic.  `aux` 2 marks the load non-temporal.
 template <int V>
-__device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V]) {
+__device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, float (&x)[V],
+                                                int second_at = 4) {
     if constexpr (V == 8) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         // the second half of a switched-off lane stays out of range: 0xffffffff + 16 would wrap into it
-        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 16u;
+        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 4u * (unsigned)second_at;
         const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
         const f4 u = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, second, 0, 0));
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; x[4] = u.x; x[5] = u.y; x[6] = u.z; x[7] = u.w;
@@ -178,11 +200,12 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
 
 // AUX 2 marks the store non-temporal (the line need not stay in the L2).
 template <int V, int AUX = 0>
-__device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V]) {
+__device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V],
+                                                 int second_at = 4) {
     if constexpr (V == 8) {
         typedef float f4 __attribute__((ext_vector_type(4)));
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
-        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 16u;
+        const unsigned second = byte_offset == kOutOfRange ? kOutOfRange : byte_offset + 4u * (unsigned)second_at;
         const f4 t = {x[0], x[1], x[2], x[3]};
         const f4 u = {x[4], x[5], x[6], x[7]};
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, t), rsrc, byte_offset, 0, AUX);
@@ -212,10 +235,10 @@ __device__ __forceinline__ void buffer_store_vec(__amdgpu_buffer_rsrc_t rsrc, un
 // beta == 0 the old value is not read, so the output buffer may hold anything beforehand.
 struct Scaling { float alpha, beta; };
 template <int V, bool DWORD_ALIGNED = false>
-__device__ __forceinline__ void scale_into(float (&v)[V], const float* __restrict__ old, Scaling s) {
+__device__ __forceinline__ void scale_into(float (&v)[V], const float* __restrict__ old, Scaling s, int second_at = 4) {
     if (s.beta != 0.0f) {
         float o[V];
-        if constexpr (DWORD_ALIGNED) load_vec_dword_aligned<V>(old, o); else load_vec<V>(old, o);
+        if constexpr (DWORD_ALIGNED) load_vec_dword_aligned<V>(old, o, second_at); else load_vec<V>(old, o);
 #pragma unroll
         for (int i = 0; i < V; ++i) v[i] = fmaf(s.alpha, v[i], s.beta * o[i]);
     } else {
@@ -225,10 +248,11 @@ __device__ __forceinline__ void scale_into(float (&v)[V], const float* __restric
 }
 // the same with the old value behind a buffer descriptor (a switched-off lane reads zeros)
 template <int V>
-__device__ __forceinline__ void scale_into(float (&v)[V], __amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, Scaling s) {
+__device__ __forceinline__ void scale_into(float (&v)[V], __amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, Scaling s,
+                                           int second_at = 4) {
     if (s.beta != 0.0f) {                           // wave-uniform
         float o[V];
-        buffer_load_vec<V>(rsrc, byte_offset, o);
+        buffer_load_vec<V>(rsrc, byte_offset, o, second_at);
 #pragma unroll
         for (int i = 0; i < V; ++i) v[i] = fmaf(s.alpha, v[i], s.beta * o[i]);
     } else {

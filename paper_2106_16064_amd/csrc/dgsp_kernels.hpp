@@ -515,6 +515,13 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     const ChunkPlan plan = plan_chunks(rowptr, M, 6);        // quanta of one wave's width
     const unsigned nnz = plan.nnz;
     const unsigned long long y_elems = dense_bytes(M, ldy, N) / 4ull;
+    // V = 8: the lane's second four columns start here.  N = 5, 6, 7 (one pass, n0 = 0): at N - 4, overlapping
+    // the first four; the shared columns get the same sums twice and are added to memory once.
+    const int second = (V == 8 && N - n0 < 8) ? N - n0 - 4 : 4;
+
+    auto add_to_row = [&](float* y, const float (&v)[V]) {
+        if constexpr (V == 8) atomic_add_halves(y, v, second); else atomic_add_vec<V>(y, v);
+    };
 
     for (unsigned sub = 0; sub < kSubRanges; ++sub) {
     unsigned d0, d1;
@@ -530,8 +537,8 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
             float out[V];
 #pragma unroll
             for (int i = 0; i < V; ++i) out[i] = 0.0f;
-            if constexpr (AXPBY) scale_into<V, true>(out, y, sc);
-            store_vec_dword_aligned<V>(y, out);
+            if constexpr (AXPBY) scale_into<V, true>(out, y, sc, second);
+            store_vec_dword_aligned<V>(y, out, second);
         }
         continue;
     }
@@ -622,10 +629,10 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         if (x_small) {
 #pragma unroll
             for (int e = 0; e < E; ++e)
-                buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e]);
+                buffer_load_vec<V>(rx, e * kWave + lane < nE ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e], second);
         } else {
 #pragma unroll
-            for (int e = 0; e < E; ++e) load_vec_dword_aligned<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * ldx + n0, x[e]);
+            for (int e = 0; e < E; ++e) load_vec_dword_aligned<V>(X + (size_t)(e * kWave + lane < nE ? c[e] : 0) * ldx + n0, x[e], second);
         }
         {
             const bool more = d1 - ds > (unsigned)W;       // past the chunk's last tile the loads are switched off
@@ -725,11 +732,11 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 #pragma unroll
                         for (int i = 0; i < V; ++i) val[i] *= sc.alpha;          // lands on beta * Y (prepare)
                     } else {
-                        scale_into<V>(val, yrows, off, sc);
+                        scale_into<V>(val, yrows, off, sc, second);
                     }
                 }
-                buffer_store_vec<V>(yrows, off, val);
-                if (live && shared) atomic_add_vec<V>(Y + (size_t)(is + t) * ldy + n0, val);
+                buffer_store_vec<V>(yrows, off, val, second);
+                if (live && shared) add_to_row(Y + (size_t)(is + t) * ldy + n0, val);
             };
             write_rows(0);
             for (int k = 1; k * kWave < nrows; ++k) write_rows(k);
@@ -753,7 +760,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 #pragma unroll
         for (int i = 0; i < V; ++i) carry[i] *= sc.alpha;
     }
-    if (any && lane == 0 && is < M) atomic_add_vec<V>(Y + (size_t)is * ldy + n0, carry);
+    if (any && lane == 0 && is < M) add_to_row(Y + (size_t)is * ldy + n0, carry);
     }   // next chunk
 }
 

@@ -114,7 +114,7 @@ def test_selection_rules_follow_the_decision_tree():
         dg.dgsp_set_thresholds(t)
         assert dg.dgsp_select_algo(feat(64, 1.5), 8) == dg.NB_PR           # balanced, and 8 columns fit one lane
         assert dg.dgsp_select_algo(feat(64, 1.5), 16) == dg.NB_SR
-        assert dg.dgsp_select_algo(feat(64, 1.5), 7) == dg.NB_SR
+        assert dg.dgsp_select_algo(feat(64, 1.5), 7) == dg.NB_PR           # 5, 6, 7 too: its two groups of four overlap
         assert dg.dgsp_select_algo(feat(64, 0.1), 8) == dg.RS_SR           # even rows: row-split as before
         t.big_x_bytes_min, t.big_x_cv_max, t.big_x_avg_row_max = 6_000_000, 0.2, 64.0     # the added large-X rule
         t.pr_nnz_max = 2**62
