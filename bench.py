@@ -21,6 +21,7 @@ and writes its per-cell records under RESULTS_DIR):
     --suite ablation  each optimisation against the kernel without it, on 27 R-MAT matrices
     --suite tiny      the launch-bound 4096^2 configuration, eager launches against HIP graph replay
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
+    --suite widths    the adaptive call at 34 dense widths from 1 to 128 on three matrices
 """
 from __future__ import annotations
 
@@ -437,6 +438,34 @@ def run_size(args):
     return 0
 
 
+def run_widths(args):
+    """The adaptive call over a range of dense widths, multiples of four and not, on three matrix kinds:
+    time per call and the kernel the rules picked (what a caller with an odd N gets)."""
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_widths.jsonl")
+    widths = list(range(1, 21)) + [24, 31, 32, 33, 40, 41, 47, 48, 63, 64, 65, 96, 100, 128]
+    mats = [("R-MAT 2^20, avg degree 16", lambda: wl.rmat_csr(20, 16, seed=0, values="uniform01")),
+            ("Poisson(16) rows, 2^18 rows", lambda: wl.sweep_csr(1 << 18, 16, "poisson", 0)),
+            ("27-point stencil 64^3", lambda: wl.stencil27_csr(64, seed=0))]
+    cells = 0
+    with open(path, "w") as fh:
+        for label, gen in mats:
+            A = gen()
+            for n in widths:
+                rot = Rotation(A, wl.dense_matrix(A.K, n, "uniform", seed=0))
+                us = median(time_events(None, lambda i: rot.step(i, dg.AUTO), max(5, min(args.steps, 30)), 3)) * 1e3
+                sel = dg.dgsp_algo_name(dg.dgsp_select_algo(rot.mats[0].features, n))
+                fh.write(json.dumps({"matrix": label, "N": n, "nnz": A.nnz, "us": us, "selected": sel}) + "\n")
+                fh.flush()
+                cells += 1
+                del rot
+            print(f"[widths] {label} done", file=sys.stderr, flush=True)
+    print(json.dumps({"suite": "widths", "cells": cells, "file": path}))
+    return 0
+
+
 def run_ablation(args):
     """Each optimisation of Section 2.1 against the kernel without it, on a grid of 27 R-MAT matrices
     (3 sizes x 3 densities x 3 skews; the paper's own 27 parameter sets are not published):
@@ -621,7 +650,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -643,7 +672,7 @@ def main():
     from paper_2106_16064_amd import binding as dg
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
-            "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel}[args.suite](args)
+            "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel, "widths": run_widths}[args.suite](args)
 
 
 if __name__ == "__main__":
