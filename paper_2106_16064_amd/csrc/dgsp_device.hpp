@@ -178,12 +178,10 @@ __device__ __forceinline__ void buffer_load_vec(__amdgpu_buffer_rsrc_t rsrc, uns
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; x[4] = u.x; x[5] = u.y; x[6] = u.z; x[7] = u.w;
     } else if constexpr (V == 4) {
         typedef float f4 __attribute__((ext_vector_type(4)));
-        typedef unsigned u4 __attribute__((ext_vector_type(4)));
         const f4 t = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
     } else if constexpr (V == 2) {
         typedef float f2 __attribute__((ext_vector_type(2)));
-        typedef unsigned u2 __attribute__((ext_vector_type(2)));
         const f2 t = __builtin_bit_cast(f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, 0));
         x[0] = t.x; x[1] = t.y;
     } else if constexpr (V == 3) {
