@@ -142,9 +142,10 @@ typedef struct {
  *             beta = 0); rows of A without entries give exact zeros.  Must not
  *             overlap X.
  *   algo      a dgsp_algo_t.  DGSP_AUTO here, where no features are known,
- *             means: nnz-balanced, parallel reduction if N <= n_parallel_max,
- *             else nnz-balanced sequential (the variants that are safe for
- *             any row-length distribution).
+ *             means: nnz-balanced, parallel reduction if N <= max(n_parallel_max,
+ *             wide_parallel_n) (8 by default: one pass over the matrix), else
+ *             nnz-balanced sequential (the variants that are safe for any
+ *             row-length distribution).
  *   stream    hipStream_t as void*, NULL = default stream.
  *
  * Every algo accepts every N >= 1 and any (float) alignment of X and Y; no

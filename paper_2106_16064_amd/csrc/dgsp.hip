@@ -439,7 +439,13 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
     if (!rowptr || !Y) return DGSP_ERR_INVALID_ARG;
     if (nnz > 0 && (!colidx || !vals || !X || K == 0)) return DGSP_ERR_INVALID_ARG;
 
-    if (algo == DGSP_AUTO) algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
+    // no row statistics: the balanced kernels are safe for any row-length distribution; the parallel one while
+    // it needs a single pass over the matrix (it was the faster of the two on 22 of 24 sweep matrices at N = 8)
+    if (algo == DGSP_AUTO) {
+        const int64_t one_pass = g_thresholds.wide_parallel_n > g_thresholds.n_parallel_max ? g_thresholds.wide_parallel_n
+                                                                                            : g_thresholds.n_parallel_max;
+        algo = (N <= one_pass) ? DGSP_NB_PR : DGSP_NB_SR;
+    }
 
     Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, hints.col_span, hints.cv_row, switches};
     if (scaling) { p.scaled = true; p.alpha = scaling->alpha; p.beta = scaling->beta; }
