@@ -27,12 +27,31 @@ def transpose_csr(A: CsrMatrix) -> CsrMatrix:
                      A.vals[order].astype(np.float32), A.name + "^T", {})
 
 
-class SparseOperator:
-    """A and A^T on the device; ``op(X)`` is differentiable with respect to X."""
+def transpose_device_csr(A: "dg.DeviceCsr") -> "dg.DeviceCsr":
+    """A^T of a matrix that lives on the GPU, built there with PyTorch's sort / bincount / cumsum (data
+    movement only: set-up, not part of the product).  Same layout as ``transpose_csr``: entries grouped by
+    column, rows ascending inside a group."""
+    import torch
+    lens = (A.rowptr[1:] - A.rowptr[:-1]).to(torch.int64)
+    rows = torch.repeat_interleave(torch.arange(A.M, device=A.rowptr.device, dtype=torch.int64), lens)
+    cols = A.colidx.to(torch.int64)
+    order = torch.argsort(cols, stable=True)
+    rowptr = torch.zeros(A.K + 1, dtype=torch.int64, device=A.rowptr.device)
+    rowptr[1:] = torch.cumsum(torch.bincount(cols, minlength=A.K), 0)
+    return dg.DeviceCsr.from_device(A.K, A.M, rowptr, rows[order], A.vals[order])
 
-    def __init__(self, A: CsrMatrix, device="cuda:0"):
-        self.fwd = dg.DeviceCsr(A, device)
-        self.bwd = dg.DeviceCsr(transpose_csr(A), device)
+
+class SparseOperator:
+    """A and A^T on the device; ``op(X)`` is differentiable with respect to X.  ``A`` is a host ``CsrMatrix``
+    or a ``DeviceCsr`` (e.g. ``DeviceCsr.from_torch_sparse_csr``), whose transpose is then built on the GPU."""
+
+    def __init__(self, A, device="cuda:0"):
+        if isinstance(A, dg.DeviceCsr):
+            self.fwd = A
+            self.bwd = transpose_device_csr(A)
+        else:
+            self.fwd = dg.DeviceCsr(A, device)
+            self.bwd = dg.DeviceCsr(transpose_csr(A), device)
 
     def __call__(self, X, algo=dg.AUTO):
         return _SpMM.apply(X, self, algo)

@@ -750,6 +750,32 @@ def test_matrix_that_is_already_on_the_device(dg):
         assert ok, (N, worst)
 
 
+def test_gradient_when_the_matrix_lives_on_the_device_only(dg):
+    """The operator built from device arrays: its transpose is made on the GPU and must hold exactly the arrays
+    the host transpose gives; forward and gradient against the oracle."""
+    import torch
+    from paper_2106_16064_amd.autograd import SparseOperator, transpose_csr
+    A = wl.rmat_csr(scale=12, avg_degree=9, seed=21)
+    dA = dg.DeviceCsr.from_device(A.M, A.K, torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colidx).cuda(),
+                                  torch.from_numpy(A.vals).cuda())
+    op = SparseOperator(dA)
+    T = transpose_csr(A)
+    assert np.array_equal(op.bwd.rowptr.cpu().numpy(), T.rowptr) and np.array_equal(op.bwd.colidx.cpu().numpy(), T.colidx)
+    assert np.array_equal(op.bwd.vals.cpu().numpy(), T.vals) and (op.bwd.M, op.bwd.K) == (A.K, A.M)
+    N = 8
+    X = wl.dense_matrix(A.K, N, "normal", seed=5)
+    Gy = wl.dense_matrix(A.M, N, "uniform", seed=6)
+    dX = torch.from_numpy(X).cuda().requires_grad_(True)
+    Y = op(dX)
+    Y.backward(torch.from_numpy(Gy).cuda())
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    ok, worst = oracle.within_bound(Y.detach().cpu().numpy(), yref, bnd, TOL)
+    assert ok, worst
+    gref, gbnd = oracle.spmm_ref(T.M, T.K, N, T.rowptr, T.colidx, T.vals, Gy)
+    ok, worst = oracle.within_bound(dX.grad.cpu().numpy(), gref, gbnd, TOL)
+    assert ok, worst
+
+
 # ------------------------------------------------------------------ widths that are no multiple of the vector width
 @pytest.mark.parametrize("N", [3, 5, 6, 7, 9, 41, 47, 63, 65, 66, 67, 129, 130, 257, 300])
 def test_widths_that_are_no_multiple_of_four(dg, N):
