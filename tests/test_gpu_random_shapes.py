@@ -9,7 +9,7 @@ import oracle
 from paper_2106_16064_amd import workloads as wl
 
 TOL = 1e-5
-WIDTHS = (1, 1, 2, 2, 3, 4, 4, 5, 7, 8, 8, 12, 16, 24, 31, 32, 33, 64, 65, 100, 128, 130, 256, 300)
+WIDTHS = (1, 1, 2, 2, 3, 4, 4, 5, 6, 7, 8, 8, 9, 10, 12, 16, 24, 31, 32, 33, 64, 65, 100, 128, 130, 256, 300)
 
 
 def random_row_lengths(rng, M, K):
