@@ -484,7 +484,9 @@ constexpr unsigned kNoRow = 0xffffffffu;
 //      one per 64 entries).
 //   5. The rows that end in a tile are consecutive, so finished sums are put
 //      into LDS by row and written out together: lane l stores row is + l.
-//      Rows without entries keep the zero the buffer was cleared to.
+//      Rows without entries keep the zero the buffer was cleared to.  The
+//      store of the first 64 rows is issued a tile later, behind that tile's
+//      loads.
 //   6. The sum still open at the end of a tile is handed to the chunk's next
 //      tile in a register; only the two ends of a chunk can need an atomic add.
 //
@@ -585,6 +587,24 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     load_entries(js, true, cA, aA);
     unsigned ds = d0;
 
+    // The first 64 row results of a tile are stored one tile later, after the next tile's loads have been issued:
+    // the memory pipeline retires loads and stores in issue order, so a store in front of the gathers would put
+    // its own round trip into their wait.
+    float pending_val[V];
+    unsigned pending_off = kOutOfRange;
+    unsigned long long pending_first = 0ull;             // first element of the rows the pending store addresses
+#pragma unroll
+    for (int i = 0; i < V; ++i) pending_val[i] = 0.0f;
+    auto rows_descriptor = [&](unsigned long long first_elem) {
+        const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
+        return __builtin_amdgcn_make_buffer_rsrc((void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left,
+                                                 kBufferFlags);
+    };
+    auto store_pending = [&]() {
+        buffer_store_vec<V>(rows_descriptor(pending_first), pending_off, pending_val, second);
+        pending_off = kOutOfRange;
+    };
+
     // one tile: consumes (c, a, w_end), leaves the next tile's loads in flight in (c2, a2, w_end2)
     auto do_tile = [&](int (&c)[E], float (&a)[E], unsigned w_end, int (&c2)[E], float (&a2)[E], unsigned& w_end2) {
         const unsigned de = (d1 - ds > (unsigned)W) ? ds + W : d1;
@@ -639,6 +659,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
             load_row_bounds(ie, more, w_unused, w_end2);
             load_entries(je, more, c2, a2);
         }
+        store_pending();                                   // the previous tile's rows
 
         // ---- products change hands through LDS: entry 64e+l -> lane (64e+l)/E
 #pragma unroll
@@ -717,9 +738,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         //      buffer store, further batches (tiles crowded with short rows) in a loop
         {
             const unsigned long long first_elem = (unsigned long long)is * (unsigned)ldy + (unsigned)n0;
-            const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
-            __amdgpu_buffer_rsrc_t yrows = __builtin_amdgcn_make_buffer_rsrc(
-                (void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left, kBufferFlags);
+            __amdgpu_buffer_rsrc_t yrows = rows_descriptor(first_elem);
             auto write_rows = [&](int k) {
                 const int t = k * kWave + lane;                     // local row
                 float val[V];
@@ -735,7 +754,13 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
                         scale_into<V>(val, yrows, off, sc, second);
                     }
                 }
-                buffer_store_vec<V>(yrows, off, val, second);
+                if (k == 0) {
+                    pending_first = first_elem; pending_off = off;
+#pragma unroll
+                    for (int i = 0; i < V; ++i) pending_val[i] = val[i];
+                } else {
+                    buffer_store_vec<V>(yrows, off, val, second);
+                }
                 if (live && shared) add_to_row(Y + (size_t)(is + t) * ldy + n0, val);
             };
             write_rows(0);
@@ -752,6 +777,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
         do_tile(cB, aB, wB, cA, aA, wA);
     }
 
+    store_pending();                                       // the last tile's rows
     // the row still open at the end of my chunk is finished by another wave
     bool any = false;
 #pragma unroll
