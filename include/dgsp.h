@@ -194,8 +194,10 @@ int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N,
  */
 int dgsp_select_algo(const dgsp_features_t *features, int64_t N);
 
-/* Read / replace the thresholds used by dgsp_select_algo (process-wide, not
- * thread-safe against concurrent selection).  Host pointers. */
+/* Read / replace the thresholds used by dgsp_select_algo (process-wide; reads
+ * and writes are serialised by a lock, every selection sees one consistent set).
+ * They steer the CHOICE of kernel only: the launch geometry of a kernel asked for
+ * by name does not depend on them.  Host pointers. */
 void dgsp_get_thresholds(dgsp_thresholds_t *out);
 void dgsp_set_thresholds(const dgsp_thresholds_t *in);
 
@@ -275,10 +277,14 @@ int dgsp_spmm_csr_phase(int64_t M, int64_t K, int64_t N, int64_t nnz,
  * Only the N used columns of a row are read or written; what lies between rows is
  * not touched.  This is what a column slice of a wider row-major matrix needs
  * (the dense columns shared out between devices, or processed a slice at a time).
- * The vector width of the dense-row accesses (Section 2.1.2) additionally needs
- * ldx and ldy to be multiples of it.  algo may be DGSP_AUTO: with features the
- * rules choose, without them the balanced kernel for the width.  Everything else
- * as dgsp_spmm_csr_nnz; `features` may be NULL (host pointer otherwise).
+ * The vector width of the dense-row accesses (Section 2.1.2) depends on N only,
+ * not on ldx, ldy or the alignment of the views (see dgsp_spmm_csr); rows that
+ * start on 128-byte lines are merely fetched with fewer requests.  algo may be
+ * DGSP_AUTO: with features the rules choose, without them the balanced kernel
+ * for the width; where ldy exceeds the balanced kernels' limit of 2^20 floats the
+ * library's own choice falls to DGSP_RS_SR (a balanced kernel asked for by name
+ * returns DGSP_ERR_UNSUPPORTED there).  Everything else as dgsp_spmm_csr_nnz;
+ * `features` may be NULL (host pointer otherwise).
  */
 int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz,
                      const int32_t *rowptr, const int32_t *colidx, const float *vals,

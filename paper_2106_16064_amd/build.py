@@ -47,15 +47,16 @@ def build(verbose: bool = True, extra_flags=()) -> Path:
     return LIB
 
 
-EXAMPLE_SRC = CSRC / "c_abi_example.c"
-EXAMPLE = HERE / "c_abi_example"
+EXAMPLE_SRC = HERE.parent / "tests" / "c_abi_example.c"
+EXAMPLE = HERE.parent / "tests" / "c_abi_example"
 
 
 def build_c_example(verbose: bool = True) -> Path:
-    """A plain-C caller of the library (gcc, no C++): shows and tests the C-ABI from outside Python."""
+    """A plain-C caller of the library (gcc, no C++; a test program that lives under tests/): exercises the
+    C-ABI from outside Python."""
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
     cmd = ["gcc", "-std=c11", "-O2", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include", "-o", str(EXAMPLE), str(EXAMPLE_SRC),
-           f"-L{HERE}", "-ldgsp", f"-L{rocm}/lib", "-lamdhip64", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{rocm}/lib", "-lm"]
+           f"-L{HERE}", "-ldgsp", f"-L{rocm}/lib", "-lamdhip64", "-Wl,-rpath,$ORIGIN/../paper_2106_16064_amd", f"-Wl,-rpath,{rocm}/lib", "-lm"]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -44,13 +44,6 @@ inline int ilog2_ceil(long long v) {   // smallest l with 2^l >= v  (v >= 1)
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// widest vector width that N and the buffers allow (Section 2.1.2: float2 / float4)
-inline int widest_vector(long long N, const float* X, const float* Y) {
-    if (N % 4 == 0 && aligned(X, 16) && aligned(Y, 16)) return 4;
-    if (N % 2 == 0 && aligned(X, 8) && aligned(Y, 8)) return 2;
-    return 1;
-}
-
 inline unsigned clamp_blocks(long long want, long long cap) {
     if (want < 1) want = 1;
     return (unsigned)(want < cap ? want : cap);
@@ -61,7 +54,12 @@ constexpr int kBlocksPerCu = 8;
 
 static_assert((1 << kNbSrLogTile) == kNbSrTile, "tile must be a power of two");
 
-extern dgsp_thresholds_t g_thresholds;      // the selector's state, defined further down
+// Rows count as "about equally long" for the launch geometry of the row-split sequential kernel when the
+// caller's statistics give a coefficient of variation up to this (a property of the kernel's schedule, fixed
+// here; the selector's thresholds are separate state and do not reach the launch code).
+constexpr double kEvenRowsCvMax = 0.3;
+// largest leading dimension of Y the balanced kernels take (a tile's rows are stored through 32-bit byte offsets)
+constexpr int64_t kBalancedLdyMax = 1 << 20;
 
 // What a caller's row statistics tell the launch code (nothing, when it passed none).
 struct Hints {
@@ -85,9 +83,14 @@ struct Problem {
     float alpha = 1.0f, beta = 0.0f;
 };
 
-inline int vector_width(const Problem& p) {
+// Vector width of the comparison kernel without LDS staging (rs_sr_direct_kernel) only: it uses plain
+// float2 / float4 accesses, which need N, the leading dimensions and the addresses of X and Y to fit.
+// The four kernels proper do not depend on alignment (see pr_vector_width, sr_shape).
+inline int direct_kernel_vector_width(const Problem& p) {
     if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return 1;
-    int v = widest_vector(p.N, p.X, p.Y);
+    int v = 1;
+    if (p.N % 4 == 0 && aligned(p.X, 16) && aligned(p.Y, 16)) v = 4;
+    else if (p.N % 2 == 0 && aligned(p.X, 8) && aligned(p.Y, 8)) v = 2;
     while (v > 1 && (p.ldx % v != 0 || p.ldy % v != 0)) v >>= 1;     // every row must start aligned
     return v;
 }
@@ -219,7 +222,7 @@ int launch_rs_sr_v(const Problem& p) {
     // dense columns as in the balanced kernel, four rows per wave in step; 2-16 % faster at N >= 128 on such matrices.
     // With long rows among short ones the rows of a wave wait for the longest (+30 % measured), and without row
     // statistics nothing is known: then a group spans the whole width.
-    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= g_thresholds.sr_cv_min;
+    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= kEvenRowsCvMax;
     const SrColumns cols = sr_columns(p.N, V, even_rows && p.N >= 128);
     const int logG = cols.logG;
     const unsigned col_blocks = cols.blocks;
@@ -241,7 +244,7 @@ int launch_rs_sr_v(const Problem& p) {
 template <int V>
 int launch_rs_sr_direct_v(const Problem& p) {
     // the same column blocks as the kernel it is compared with
-    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= g_thresholds.sr_cv_min;
+    const bool even_rows = p.cv_row >= 0.0 && p.cv_row <= kEvenRowsCvMax;
     const SrColumns cols = sr_columns(p.N, V, even_rows && p.N >= 128);
     const int logG = cols.logG;
     const unsigned col_blocks = cols.blocks;
@@ -269,7 +272,7 @@ int launch_rs_sr_pick(const Problem& p) {
 
 int launch_rs_sr(const Problem& p) {
     if (p.switches & DGSP_ABL_NO_SPARSE_STAGING) {
-        switch (vector_width(p)) {
+        switch (direct_kernel_vector_width(p)) {
             case 4: return launch_rs_sr_direct_v<4>(p);
             case 2: return launch_rs_sr_direct_v<2>(p);
             default: return launch_rs_sr_direct_v<1>(p);
@@ -332,7 +335,7 @@ int launch_nb_pr_v(const Problem& p) {
     constexpr unsigned tile = kWave * 4 * KQ;
     const unsigned col_groups = (unsigned)((p.N + V - 1) / V);      // V = 8 also takes N = 5, 6, 7: one group
     // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
-    if (col_groups > 65535u || p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
+    if (col_groups > 65535u || p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
@@ -373,7 +376,7 @@ int launch_nb_sr_v(const Problem& p) {
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
-    if (p.ldy > (1 << 20)) return DGSP_ERR_UNSUPPORTED;
+    if (p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
     const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
@@ -409,6 +412,7 @@ int launch_nb_sr(const Problem& p) {
 // ---------------------------------------------------------------- selector state
 // Defaults fitted on MI355X on the 24-matrix synthetic sweep, pr_nnz_max on larger
 // banded and random matrices (the paper prints no threshold values, Section 2.2).
+std::mutex g_thresholds_mu;                 // guards g_thresholds: readers take a copy
 dgsp_thresholds_t g_thresholds = {
     /* n_parallel_max  */ 4,
     /* pr_avg_row_min  */ 48.0,
@@ -423,6 +427,18 @@ dgsp_thresholds_t g_thresholds = {
     /* big_x_cv_max      */ 0.2,
     /* big_x_avg_row_max */ 64.0,
 };
+
+dgsp_thresholds_t thresholds_snapshot() {
+    std::lock_guard<std::mutex> lock(g_thresholds_mu);
+    return g_thresholds;
+}
+
+// The balanced kernels address the rows of a tile through 32-bit byte offsets and stop at a leading dimension
+// of 2^20 floats (DGSP_ERR_UNSUPPORTED when asked for by name).  A choice the library makes itself moves to the
+// row-split sequential kernel there, which has no such limit (so wide a Y means N or the stride is huge).
+inline int library_choice(int algo, int64_t ldy) {
+    return ((algo == DGSP_NB_SR || algo == DGSP_NB_PR) && ldy > kBalancedLdyMax) ? DGSP_RS_SR : algo;
+}
 
 int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
         const float* vals, const float* X, float* Y, int algo, void* stream, int phase = DGSP_PHASE_ALL,
@@ -442,9 +458,9 @@ int run(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, con
     // no row statistics: the balanced kernels are safe for any row-length distribution; the parallel one while
     // it needs a single pass over the matrix (it was the faster of the two on 22 of 24 sweep matrices at N = 8)
     if (algo == DGSP_AUTO) {
-        const int64_t one_pass = g_thresholds.wide_parallel_n > g_thresholds.n_parallel_max ? g_thresholds.wide_parallel_n
-                                                                                            : g_thresholds.n_parallel_max;
-        algo = (N <= one_pass) ? DGSP_NB_PR : DGSP_NB_SR;
+        const dgsp_thresholds_t t = thresholds_snapshot();
+        const int64_t one_pass = t.wide_parallel_n > t.n_parallel_max ? t.wide_parallel_n : t.n_parallel_max;
+        algo = library_choice((N <= one_pass) ? DGSP_NB_PR : DGSP_NB_SR, ldy);
     }
 
     Problem p{(int)M, (int)N, (int)ldx, (int)ldy, K, nnz, rowptr, colidx, vals, X, Y, (hipStream_t)stream, phase, hints.col_span, hints.cv_row, switches};
@@ -488,7 +504,7 @@ extern "C" int dgsp_spmm_csr_ld(int64_t M, int64_t K, int64_t N, int64_t nnz, co
     if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
     if (features && nnz < 0) nnz = features->nnz;
     if (algo == DGSP_AUTO && features && N >= 1) {
-        algo = dgsp_select_algo(features, N);
+        algo = library_choice(dgsp_select_algo(features, N), ldy);
     }
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                Hints(features), 0, ldx, ldy);
@@ -501,7 +517,7 @@ extern "C" int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
     if (ldx < N || ldy < N) return DGSP_ERR_INVALID_ARG;
     if (features && nnz < 0) nnz = features->nnz;
     if (algo == DGSP_AUTO && features && N >= 1) {
-        algo = dgsp_select_algo(features, N);
+        algo = library_choice(dgsp_select_algo(features, N), ldy);
     }
     const Scaling sc{alpha, beta};
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
@@ -524,7 +540,7 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
                                   float* Y, int* chosen, void* stream) {
     if (!features) return DGSP_ERR_INVALID_ARG;
     if (features->M != M || features->nnz < 0) return DGSP_ERR_INVALID_ARG;
-    int algo = (N >= 1) ? dgsp_select_algo(features, N) : DGSP_NB_PR;
+    int algo = (N >= 1) ? library_choice(dgsp_select_algo(features, N), N) : DGSP_NB_PR;
     if (algo < 0) return DGSP_ERR_INVALID_ARG;
     if (chosen) *chosen = algo;
     return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, Hints(features));
@@ -533,7 +549,7 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
 // Section 2.2: N picks the reduction, row-length statistics pick the partition.
 extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     if (!f || N < 1) return DGSP_AUTO;
-    const dgsp_thresholds_t& t = g_thresholds;
+    const dgsp_thresholds_t t = thresholds_snapshot();
     // all rows short: one lane group per row keeps a wave busy with no cross-lane step and no idle tail
     if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
     if (N <= t.n_parallel_max) {
@@ -552,11 +568,13 @@ extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
 }
 
 extern "C" void dgsp_get_thresholds(dgsp_thresholds_t* out) {
-    if (out) *out = g_thresholds;
+    if (out) *out = thresholds_snapshot();
 }
 
 extern "C" void dgsp_set_thresholds(const dgsp_thresholds_t* in) {
-    if (in) g_thresholds = *in;
+    if (!in) return;
+    std::lock_guard<std::mutex> lock(g_thresholds_mu);
+    g_thresholds = *in;
 }
 
 extern "C" int dgsp_features_from_rowptr_host(int64_t M, int64_t K, const int32_t* rowptr, dgsp_features_t* out) {
@@ -630,16 +648,13 @@ extern "C" int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t* 
     return DGSP_OK;
 }
 
-extern "C" int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,
-                                             void* workspace, dgsp_features_t* out, void* stream) {
-    if (M < 0 || K < 0 || !out || (!rowptr && M > 0)) return DGSP_ERR_INVALID_ARG;
-    if (M > (int64_t)INT32_MAX - 4096) return DGSP_ERR_INVALID_ARG;
+namespace {
+
+// The device pass behind both entry points: `ws` is kFeatureWords 64-bit words of device scratch.
+int features_from_csr_device(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,
+                             unsigned long long* ws, dgsp_features_t* out, hipStream_t st) {
     dgsp_features_t f{};
     f.M = M; f.K = K;
-    if (M == 0) { *out = f; return DGSP_OK; }
-    if (!workspace || !aligned(workspace, 8)) return DGSP_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    unsigned long long* ws = static_cast<unsigned long long*>(workspace);
     hipLaunchKernelGGL(features_init_kernel, dim3(1), dim3(kWave), 0, st, ws);
     const long long waves = (M + kWave - 1) / kWave;
     const dim3 grid(clamp_blocks((waves + kWavesPerBlock - 1) / kWavesPerBlock, (long long)device_info().cus * kBlocksPerCu));
@@ -659,6 +674,18 @@ extern "C" int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t
     f.col_span = (colidx && K > 0 && h[3] > 0) ? (double)h[4] / ((double)K * (double)h[3]) : 0.0;
     *out = f;
     return DGSP_OK;
+}
+
+}  // namespace
+
+extern "C" int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,
+                                             void* workspace, dgsp_features_t* out, void* stream) {
+    if (M < 0 || K < 0 || !out || (!rowptr && M > 0)) return DGSP_ERR_INVALID_ARG;
+    if (M > (int64_t)INT32_MAX - 4096) return DGSP_ERR_INVALID_ARG;
+    if (M == 0) { dgsp_features_t f{}; f.K = K; *out = f; return DGSP_OK; }
+    if (!workspace || !aligned(workspace, 8)) return DGSP_ERR_INVALID_ARG;
+    return features_from_csr_device(M, K, rowptr, colidx, static_cast<unsigned long long*>(workspace), out,
+                                    (hipStream_t)stream);
 }
 
 extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
@@ -702,7 +729,7 @@ extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const
     if (ms) for (int a = 0; a < 4; ++a) ms[a] = t[a];
     if (best_algo < 0) {
         // nothing was timed (M == 0 or N == 0: every call returns at once): any kernel will do
-        best_algo = (N <= g_thresholds.n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
+        best_algo = (N <= thresholds_snapshot().n_parallel_max) ? DGSP_NB_PR : DGSP_NB_SR;
     }
     *best = best_algo;
     return DGSP_OK;

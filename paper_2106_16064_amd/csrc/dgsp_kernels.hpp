@@ -4,10 +4,11 @@
 // Common shape of all four
 //   * 256-thread workgroups = 4 waves; every cooperative step is wave-local
 //     (DPP moves or wave-private LDS), so there is no s_barrier anywhere.
-//   * `V` (1, 2 or 4) is the vector width of dense-row accesses: one
-//     dword / dwordx2 / dwordx4 per lane (vector-type dense-row loading,
-//     Section 2.1.2).  The host picks the widest V that divides N, ldx and
-//     ldy and matches the alignment of X and Y.
+//   * `V` is the vector width of dense-row accesses: one dword / dwordx2 /
+//     dwordx3 / dwordx4 per lane, or two dwordx4 for V = 8 (vector-type
+//     dense-row loading, Section 2.1.2).  The memory pipeline takes these at
+//     any dword address, so the choice of V depends on N only, never on the
+//     alignment of X and Y or on their leading dimensions.
 //   * X and Y are row-major with leading dimensions ldx, ldy (floats per row,
 //     >= N); only the N used columns of a row are touched.
 //   * Grids are sized to the machine, not to the matrix: a wave walks a list
@@ -174,8 +175,8 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int T = kRsSrTile;
-    __shared__ int s_col[kWavesPerBlock][T];
-    __shared__ float s_val[kWavesPerBlock][T];
+    __shared__ __align__(16) int s_col[kWavesPerBlock][T];
+    __shared__ __align__(16) float s_val[kWavesPerBlock][T];
     const int lane = lane_id();
     const int wib = wave_in_block();
     int* cc = s_col[wib];
@@ -506,8 +507,9 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
                                                         Scaling sc = Scaling{1.0f, 0.0f}) {
     constexpr int E = 4 * KQ;
     constexpr int W = kWave * E;
-    __shared__ unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the tile's first entry
-    __shared__ float s_buf[kWavesPerBlock][W * V];      // products, then the tile's row results
+    // accessed 16 bytes at a time: every wave's part starts on a 16-byte boundary ((W + 4) * 4 and W * V * 4 are multiples of 16)
+    __shared__ __align__(16) unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the tile's first entry
+    __shared__ __align__(16) float s_buf[kWavesPerBlock][W * V];      // products, then the tile's row results
     const int lane = lane_id();
     const int wib = wave_in_block();
     unsigned* bnd = s_bnd[wib];
@@ -821,10 +823,10 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     constexpr int W = kNbSrTile;
     constexpr int kStoreAux = V == 4 ? 2 : 0;           // results leave non-temporal when rows are 16 bytes or more per lane
     constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
-    __shared__ int s_col[kWavesPerBlock][W];
-    __shared__ float s_val[kWavesPerBlock][W];
-    __shared__ unsigned short s_end[kWavesPerBlock][W + 8];   // end offsets (minus js) of the rows ending in the tile
-    __shared__ float s_slot[kWavesPerBlock][kSlotFloats];
+    __shared__ __align__(16) int s_col[kWavesPerBlock][W];
+    __shared__ __align__(16) float s_val[kWavesPerBlock][W];
+    __shared__ __align__(16) unsigned short s_end[kWavesPerBlock][W + 8];   // end offsets (minus js) of the rows ending in the tile
+    __shared__ __align__(16) float s_slot[kWavesPerBlock][kSlotFloats];     // slots are read 4 * V bytes at a time
     __shared__ int s_slot_row[kWavesPerBlock][kWave + 4];   // row of each slot (-1: unused)
     __shared__ int s_slot_end[kWavesPerBlock][kWave + 4];   // 1: the slot's row ended inside the tile
     const int lane = lane_id();

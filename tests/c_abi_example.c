@@ -11,7 +11,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
-#include "../../include/dgsp.h"
+#include "../include/dgsp.h"
 
 #define CHECK_HIP(call)                                                            \
     do {                                                                           \
