@@ -15,7 +15,8 @@
  *   - "device" pointers are HIP device memory of the current device, "host"
  *     pointers ordinary host memory.  The caller owns every buffer; the
  *     library allocates nothing on the device and keeps no state between
- *     calls apart from the selector thresholds (dgsp_set_thresholds).
+ *     calls apart from the selector thresholds (dgsp_set_thresholds) and the
+ *     64-byte static device array of dgsp_features_from_csr_device_noalloc.
  *   - Indices are int32, zero based.  Values are fp32, accumulation is fp32
  *     (the paper's float2/float4 loads, Section 2.1.2, imply single
  *     precision).  The summation order differs between kernels, so results
@@ -233,6 +234,25 @@ int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t *rowptr_host
 #define DGSP_FEATURES_WORKSPACE_BYTES 64
 int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t *rowptr, const int32_t *colidx,
                                   void *workspace, dgsp_features_t *out, void *stream);
+
+/*
+ * For callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture set-up, tight serving loops, harnesses that forbid hipMalloc):
+ * the same statistics as dgsp_features_from_csr_device with the 64 bytes of
+ * scratch in a static device array inside the library instead of a caller
+ * workspace.  No hipMalloc / hipFree or other allocating call is made.
+ *   - Limit: M <= DGSP_FEATURES_NOALLOC_MAX_ROWS (the int32 index range the
+ *     library has anyway; the scratch itself is 64 bytes whatever M is); larger M,
+ *     negative extents or NULL pointers -> DGSP_ERR_INVALID_ARG, nothing enqueued.
+ *   - Every call on one GPU uses that GPU's one array, cleared by a small kernel at
+ *     the start of each call: calls that overlap on one GPU (different streams or
+ *     threads) race and give wrong statistics.  Calls on different GPUs do not
+ *     interfere (each device holds its own copy, found once per device on first use).
+ *   - Like the workspace version it WAITS for its launches (result in host memory).
+ */
+#define DGSP_FEATURES_NOALLOC_MAX_ROWS (2147483647LL - 4096LL)
+int dgsp_features_from_csr_device_noalloc(int64_t M, int64_t K, const int32_t *rowptr, const int32_t *colidx,
+                                          dgsp_features_t *out, void *stream);
 
 /*
  * Profile-based selection (Section 3.1 names running all kernels once off-line

@@ -23,7 +23,7 @@ EXPORTS = (
     "dgsp_copy_f32", "dgsp_algo_name", "dgsp_status_string",
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
     "dgsp_spmm_csr_ablation", "dgsp_features_from_csr_device", "dgsp_autotune",
-    "dgsp_spmm_csr_ld", "dgsp_spmm_csr_axpby",
+    "dgsp_spmm_csr_ld", "dgsp_spmm_csr_axpby", "dgsp_features_from_csr_device_noalloc",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING = 1, 2
@@ -88,6 +88,8 @@ def lib():
         L.dgsp_spmm_csr_phase.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, ci, ctypes.POINTER(Features), vp]
         L.dgsp_features_from_csr_device.restype = ci
         L.dgsp_features_from_csr_device.argtypes = [i64, i64, vp, vp, vp, ctypes.POINTER(Features), vp]
+        L.dgsp_features_from_csr_device_noalloc.restype = ci
+        L.dgsp_features_from_csr_device_noalloc.argtypes = [i64, i64, vp, vp, ctypes.POINTER(Features), vp]
         L.dgsp_autotune.restype = ci
         L.dgsp_autotune.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ctypes.POINTER(Features), ci,
                                     ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci), vp]
@@ -220,6 +222,16 @@ def dgsp_features_from_csr_device(M, K, rowptr, colidx=None, workspace=None, str
     rc = lib().dgsp_features_from_csr_device(M, K, _ptr(rowptr), _ptr(colidx) if colidx is not None else None,
                                              _ptr(workspace), ctypes.byref(f), _stream(stream))
     _check(rc, "dgsp_features_from_csr_device")
+    return f
+
+
+def dgsp_features_from_csr_device_noalloc(M, K, rowptr, colidx=None, stream=None) -> Features:
+    """The same statistics with the scratch words in the library's static device array: the call allocates
+    nothing and takes no workspace (calls that overlap on one GPU race; waits for the result)."""
+    f = Features()
+    rc = lib().dgsp_features_from_csr_device_noalloc(M, K, _ptr(rowptr), _ptr(colidx) if colidx is not None else None,
+                                                     ctypes.byref(f), _stream(stream))
+    _check(rc, "dgsp_features_from_csr_device_noalloc")
     return f
 
 

@@ -320,6 +320,7 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
     if (parallel) {
         per_cu = tiles / (waves * kNbPrTilesPerWave);
         if (per_cu < 2) per_cu = tiles >= waves * kNbPrTilesPerWave ? 2 : 1;
+
     } else {
         // the column blocks of a wide X (grid.y) are resident side by side: count them in
         const long long want = (tiles * col_blocks + waves - 1) / waves;
@@ -686,6 +687,44 @@ extern "C" int dgsp_features_from_csr_device(int64_t M, int64_t K, const int32_t
     if (!workspace || !aligned(workspace, 8)) return DGSP_ERR_INVALID_ARG;
     return features_from_csr_device(M, K, rowptr, colidx, static_cast<unsigned long long*>(workspace), out,
                                     (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+// The statistics pass with its scratch words in a static device array.  In host code the array's name is only
+// a handle: the address a kernel can use comes from hipGetSymbolAddress, asked once per device with that
+// device current (every GPU holds its own copy of the array at its own address).
+static __device__ __align__(256) unsigned long long scratch[dgsp::kFeatureWords];     // 64 bytes per GPU
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned long long* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of `scratch` (nullptr on failure).
+unsigned long long* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<unsigned long long*>(ptr);
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int dgsp_features_from_csr_device_noalloc(int64_t M, int64_t K, const int32_t* rowptr,
+                                                     const int32_t* colidx, dgsp_features_t* out, void* stream) {
+    if (M < 0 || K < 0 || !out || (!rowptr && M > 0)) return DGSP_ERR_INVALID_ARG;
+    if (M > DGSP_FEATURES_NOALLOC_MAX_ROWS) return DGSP_ERR_INVALID_ARG;
+    if (M == 0) { dgsp_features_t f{}; f.K = K; *out = f; return DGSP_OK; }
+    unsigned long long* ws = scratch_of_current_device();
+    if (!ws) return DGSP_ERR_LAUNCH;
+    // features_init_kernel (a kernel, not a memset) clears the array first: it keeps the last call's contents
+    return features_from_csr_device(M, K, rowptr, colidx, ws, out, (hipStream_t)stream);
 }
 
 extern "C" int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
