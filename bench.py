@@ -42,11 +42,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CACHE_BYTES = 256e6 + 32e6     # Infinity Cache + 8 x 4 MB L2: what rotation has to exceed
 RESULTS_DIR = "gpurun_out"     # per-cell records of the suites
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on dgsp_copy_f32);
-# see profiles/.  None = not measured for that cell.
-MEASURED_TRAFFIC_BYTES = {
-    "nb_pr/rmat_spmv/N1": 186.8e6,   # profiles/nb_pr_kernel_rmat20_spmv.md: 181.8 MB fetched + 5.0 MB written
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE in
+# separate runs, scaled by the same counters on dgsp_copy_f32).  These are NOT measured by this run: they are
+# copied from the named summaries under profiles/, taken on the same build, and the JSON line says so
+# ("traffic_source").  A cell without an entry reports null.
+MEASURED_TRAFFIC = {
+    # "kernel/workload/N": (bytes, source)
 }
 
 
@@ -76,8 +77,20 @@ def make_workload(name, n):
         raise SystemExit(f"unknown workload {name}")
     gen, xdist, label = gens[name]
     if name not in _MATRIX_CACHE:
-        _MATRIX_CACHE.clear()          # one big matrix at a time on the host
-        _MATRIX_CACHE[name] = gen()
+        other = {"rmat_gnn": "rmat_spmv", "rmat_spmv": "rmat_gnn"}.get(name)
+        if other in _MATRIX_CACHE:
+            # the two R-MAT configurations share one pattern (same seed, same draws): only the values differ,
+            # and the generator draws them after the pattern, so regenerating would give the same arrays
+            P = _MATRIX_CACHE[other]
+            lens = P.row_lengths()
+            vals = ((1.0 / np.repeat(lens, lens).astype(np.float64)).astype(np.float32) if name == "rmat_gnn"
+                    else gen().vals)
+            new = wl.CsrMatrix(P.M, P.K, P.rowptr, P.colidx, vals, name, dict(P.meta, values=name))
+            _MATRIX_CACHE.clear()
+            _MATRIX_CACHE[name] = new
+        else:
+            _MATRIX_CACHE.clear()          # one big matrix at a time on the host
+            _MATRIX_CACHE[name] = gen()
     A = _MATRIX_CACHE[name]
     return A, wl.dense_matrix(A.K, n, xdist, seed=0), f"{label}, N={n}"
 
@@ -194,16 +207,90 @@ def copy_bandwidth(nbytes=1 << 30, reps=10):
     return 2 * nbytes / (median(ms) * 1e-3) / 1e9
 
 
-def gather_floor(rot):
-    """Time (ms) of the pure-gather probe on this matrix's column indices with N = 1: what
-    the machine needs just to stream colidx and fetch one dense value per stored entry."""
+def floor_probes(rot):
+    """Times (ms) of the committed floor probes on this workload's own arrays: the memory side of the kernels
+    with no row logic (dgsp_floor_probe).  N <= 4: stream + gather + multiply-add (and the bare gather at N = 1);
+    N a multiple of 4 from 8 on: the whole-row gather of the sequential kernels."""
     import torch
     from paper_2106_16064_amd import binding as dg
-    out = torch.empty(dg.dgsp_gather_probe_out_len(), dtype=torch.float32, device="cuda:0")
-    xs = [torch.zeros(rot.A.K, dtype=torch.float32, device="cuda:0") for _ in range(rot.copies)]
-    ms = time_events(None, lambda i: dg.dgsp_gather_probe(out, xs[i % rot.copies], rot.mats[i % rot.copies].colidx),
-                     20, 3)
-    return median(ms)
+    N, K = rot.N, rot.A.K
+    out = {}
+    modes = []
+    if N == 1:
+        modes.append(("gather_only_ms", dg.PROBE_GATHER))
+    if N in (1, 2, 4):
+        modes.append(("stream_gather_fma_ms", dg.PROBE_STREAM_GATHER_FMA))
+    if N >= 8 and N % 4 == 0:
+        modes.append(("row_gather_ms", dg.PROBE_ROW_GATHER))
+    for key, mode in modes:
+        buf = torch.empty(dg.dgsp_floor_probe_out_len(mode, N), dtype=torch.float32, device="cuda:0")
+        ms = time_events(None, lambda i: dg.dgsp_floor_probe(mode, K, N, rot.mats[i % rot.copies].colidx,
+                                                             rot.mats[i % rot.copies].vals, rot.X[i % rot.copies], buf),
+                         2 * rot.copies + 6, 3)
+        out[key] = median(ms)
+    return out
+
+
+def sampled_parity(A, X, Y, rows=20000, seed=0, tol=1e-5):
+    """The oracle on a seeded sample of rows (plus the longest row and both ends), against the same rows of the
+    GPU result Y (a host array)."""
+    import oracle
+    rng = np.random.default_rng(seed)
+    lens = A.row_lengths()
+    pick = np.unique(np.concatenate([rng.integers(0, A.M, size=min(rows, A.M)), [int(lens.argmax()), 0, A.M - 1]]))
+    plen = lens[pick].astype(np.int64)
+    rp = np.zeros(pick.size + 1, dtype=np.int64)
+    np.cumsum(plen, out=rp[1:])
+    idx = np.repeat(A.rowptr[pick].astype(np.int64) - rp[:-1], plen) + np.arange(int(rp[-1]))
+    N = X.shape[1]
+    yref, bnd = oracle.spmm_ref(pick.size, A.K, N, rp.astype(np.int32), A.colidx[idx], A.vals[idx], X)
+    ok, worst = oracle.within_bound(Y[pick], yref, bnd, tol)
+    return {"ok": bool(ok), "worst_err_over_bound": worst, "tol": tol, "rows_checked": int(pick.size)}
+
+
+def measure_cell(name, n, steps, warmup, full_parity=False):
+    """One configuration through the adaptive call: whole-call time over rotated buffers, the selected kernel's
+    main launch alone (HIP events on the launch stream), its floors, its roofline, parity against the oracle."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    A, X, label = make_workload(name, n)
+    rot = Rotation(A, X)
+    chosen = dg.dgsp_select_algo(rot.mats[0].features, n)
+    sel = dg.dgsp_algo_name(chosen)
+    ms_cold = time_steps(rot, dg.AUTO, steps, warmup, warm=False)
+    batches = max(2, steps // rot.copies)
+    ev = time_event_batches(lambda i: rot.phase(i, chosen, dg.PHASE_PREPARE),
+                            lambda i: rot.phase(i, chosen, dg.PHASE_MAIN), rot.copies, batches,
+                            max(1, warmup // rot.copies))
+    ev_ms = sum(ev) / len(ev)
+    floors = floor_probes(rot)
+    rot.step(0, dg.AUTO)
+    torch.cuda.synchronize()
+    Y = rot.Y[0].cpu().numpy()
+    if full_parity:
+        import oracle
+        yref, bnd = oracle.spmm_ref(A.M, A.K, n, A.rowptr, A.colidx, A.vals, X)
+        ok, worst = oracle.within_bound(Y, yref, bnd, 1e-5)
+        parity = {"ok": bool(ok), "worst_err_over_bound": worst, "tol": 1e-5, "rows_checked": A.M}
+    else:
+        parity = sampled_parity(A, X, Y)
+    bytes_alg = algorithmic_bytes(A, n)
+    achieved = bytes_alg / (ev_ms * 1e-3) / 1e9
+    traffic, source = MEASURED_TRAFFIC.get(f"{sel}/{name}/N{n}", (None, None))
+    cell = {
+        "workload": label, "M": A.M, "K": A.K, "nnz": A.nnz, "N": n, "buffer_rotation": rot.copies,
+        "selected_kernel": sel, "ms_per_step": ms_cold,
+        "GFLOPs": 2.0 * A.nnz * n / (ms_cold * 1e-3) / 1e9,
+        "algorithmic_bytes": bytes_alg, "effective_GBps": bytes_alg / (ms_cold * 1e-3) / 1e9,
+        "pct_hbm_peak": 100.0 * bytes_alg / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
+                     "kernel": f"dgsp::{sel}_kernel (main launch alone; HIP events on the launch stream around "
+                               f"{len(ev)} batches of {rot.copies} back-to-back launches, one per buffer set)",
+                     "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms, "floors_ms": floors},
+        "parity": parity,
+    }
+    return cell, rot, A, X
 
 
 def cpu_baseline(A, X, budget_s=8.0):
@@ -237,67 +324,63 @@ def variant_table(rot, steps, warmup):
 
 
 # ---------------------------------------------------------------------------- suites
+# The further cells of the default line: the largest single-GPU configurations of the benchmark list, which the
+# bandwidth target is stated on (GNN-style SpMM at N = 128, the stencil at N = 1 and at N = 8).
+FURTHER_CELLS = (("rmat_gnn", 128), ("stencil", 1), ("stencil", 8))
+
+
 def run_headline(args):
     import torch
     from paper_2106_16064_amd import binding as dg
-    A, X, label = make_workload(args.workload or "rmat_spmv", args.n or 1)
-    N = X.shape[1]
-    rot = Rotation(A, X)
-    f = rot.mats[0].features
-    chosen = dg.dgsp_select_algo(f, N)
-
-    ms_cold = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=False)
+    name = args.workload or "rmat_spmv"
+    N = args.n or 1
+    head, rot, A, X = measure_cell(name, N, args.steps, args.warmup, full_parity=True)
+    ms_cold = head["ms_per_step"]
     ms_warm = time_steps(rot, dg.AUTO, args.steps, args.warmup, warm=True)
-
-    # dominant kernel alone: the small prepare launch of the balanced kernels runs untimed first
-    # (once per buffer set), then one event pair brackets one main launch per buffer set
-    batches = max(1, args.steps // rot.copies)
-    ev = time_event_batches(lambda i: rot.phase(i, chosen, dg.PHASE_PREPARE),
-                            lambda i: rot.phase(i, chosen, dg.PHASE_MAIN), rot.copies, batches,
-                            max(1, args.warmup // rot.copies))
-    ev_ms = sum(ev) / len(ev)
-    kernel_name = {0: "rs_sr_kernel", 1: "rs_pr_kernel", 2: "nb_sr_kernel", 3: "nb_pr_kernel"}[chosen]
-    floor_ms = gather_floor(rot) if N == 1 else None
-
-    bytes_alg = algorithmic_bytes(A, N)
+    bytes_alg = head["algorithmic_bytes"]
     flops = 2.0 * A.nnz * N
     table = variant_table(rot, args.steps, args.warmup)
     best = min(table, key=table.get)
-    sel_name = dg.dgsp_algo_name(chosen)
+    sel_name = head["selected_kernel"]
+    baseline = cpu_baseline(A, X)
+    del rot
+    torch.cuda.empty_cache()
 
-    # parity spot check of what was just timed
-    import oracle
-    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
-    ok, worst = oracle.within_bound(rot.Y[0].cpu().numpy(), yref, bnd, 1e-5)
+    cells = []
+    if not args.workload and not args.no_cells:
+        for cname, cn in FURTHER_CELLS:
+            cell, crot, _, _ = measure_cell(cname, cn, max(10, min(args.steps, 40)), min(args.warmup, 5))
+            del crot
+            torch.cuda.empty_cache()
+            cells.append(cell)
+            print(f"[cell] {cell['workload']}: {cell['selected_kernel']} {cell['ms_per_step'] * 1e3:.1f} us per call, "
+                  f"main launch {cell['roofline']['launch_ms'] * 1e3:.1f} us, frac {cell['roofline']['frac']:.3f}, "
+                  f"parity {'ok' if cell['parity']['ok'] else 'FAIL'}", file=sys.stderr, flush=True)
 
-    achieved = bytes_alg / (ev_ms * 1e-3) / 1e9
+    roof = head["roofline"]
     out = {
         "metric": "SpMM GFLOP/s (2*nnz*N/t); effective HBM GB/s and selector loss alongside",
         "value": flops / (ms_cold * 1e-3) / 1e9, "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_cold,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": label, "M": A.M, "K": A.K, "nnz": A.nnz, "N": N,
-                   "buffer_rotation": rot.copies, "selected_kernel": sel_name},
-        "effective_GBps": bytes_alg / (ms_cold * 1e-3) / 1e9,
-        "pct_hbm_peak": 100.0 * bytes_alg / (ms_cold * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "config": {"workload": head["workload"], "M": A.M, "K": A.K, "nnz": A.nnz, "N": N,
+                   "buffer_rotation": head["buffer_rotation"], "selected_kernel": sel_name,
+                   "why_this_workload": "the benchmark list's second configuration (power-law SpMV), the one the "
+                                        "default line is defined on; the larger configurations follow under 'cells'"},
+        "effective_GBps": head["effective_GBps"], "pct_hbm_peak": head["pct_hbm_peak"],
         "warm_cache": {"ms_per_step": ms_warm, "GFLOPs": flops / (ms_warm * 1e-3) / 1e9,
                        "effective_GBps": bytes_alg / (ms_warm * 1e-3) / 1e9},
         "copy_kernel_GBps": copy_bandwidth(),
         "selector": {"chosen": sel_name, "best": best, "loss_vs_best": table[sel_name] / table[best] - 1.0,
                      "median_ms": table},
-        "parity": {"ok": ok, "worst_err_over_bound": worst, "tol": 1e-5},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{sel_name}/{args.workload or 'rmat_spmv'}/N{N}"),
-                     "kernel": f"dgsp::{kernel_name} (main launch alone; HIP events around {len(ev)} batches of "
-                               f"{rot.copies} back-to-back launches, one per buffer set)",
-                     "algorithmic_bytes": bytes_alg, "launch_ms": ev_ms,
-                     "gather_probe_ms": floor_ms},
-        "cpu_baseline": cpu_baseline(A, X),
+        "parity": head["parity"],
+        "roofline": roof,
+        "cpu_baseline": baseline,
+        "cells": cells,
     }
     print(json.dumps(out))
-    return 0 if ok else 1
+    return 0 if head["parity"]["ok"] and all(c["parity"]["ok"] for c in cells) else 1
 
 
 def run_configs(args):
@@ -657,6 +740,7 @@ def main():
     ap.add_argument("--warm", action="store_true", help="kernel suite: reuse one buffer set (cache-warm)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="kernel suite: also run five 1 GiB dgsp_copy_f32 launches (byte-counter calibration)")
+    ap.add_argument("--no-cells", action="store_true", help="default suite: only the headline workload, no further cells")
     ap.add_argument("--sweep-m", type=int, default=1 << 18)
     ap.add_argument("--out", default=None)
     args = ap.parse_args()

@@ -343,11 +343,19 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                sparse-row caching is measured against
  *                                (Section 2.1.3).  Only DGSP_RS_SR, else
  *                                DGSP_ERR_UNSUPPORTED.
+ *   DGSP_ABL_ITEM_TILES          the balanced parallel kernel with its chunks cut into tiles of
+ *                                merge-path items (entries + row ends), where a tile's gathers can
+ *                                only be requested after the previous tile's row ends are counted;
+ *                                DGSP_NB_PR runs blocks of entries instead, whose addresses are known
+ *                                ahead, and keeps the next block's gathers in flight during the row
+ *                                logic.  The comparison for that design choice.  Only DGSP_NB_PR,
+ *                                else DGSP_ERR_UNSUPPORTED.
  * Unknown bits -> DGSP_ERR_INVALID_ARG.  algo must be one of the four kernels.
  * `features` may be NULL (host pointer otherwise; nnz and col_span are used).
  */
 #define DGSP_ABL_SCALAR_DENSE_LOADS 1
 #define DGSP_ABL_NO_SPARSE_STAGING 2
+#define DGSP_ABL_ITEM_TILES 4
 int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz,
                            const int32_t *rowptr, const int32_t *colidx, const float *vals,
                            const float *X, float *Y, int algo, int switches,
@@ -365,6 +373,30 @@ int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz,
  */
 int dgsp_gather_probe(float *out, const float *x, const int32_t *idx, int64_t n, void *stream);
 int64_t dgsp_gather_probe_out_len(void);
+
+/*
+ * Measurement aids, not part of the method: the memory side of the kernels with no row logic at all, as floors
+ * to hold the kernels against (Section 2.1.2 names the scattered dense reads as the cost of the parallel
+ * reduction, Section 2.1.3 the contiguous dense-row reads as the strength of the sequential one).  All read
+ * colidx (and vals) once, in order, and X where the columns say; none knows about rows.
+ *   DGSP_PROBE_GATHER             N = 1: dgsp_gather_probe (stream colidx, gather x[colidx], nothing else)
+ *   DGSP_PROBE_STREAM_GATHER_FMA  N in {1, 2, 4}: stream colidx and vals in blocks of 512 entries, gather N
+ *                                 values of X per entry with one vector load, multiply-add; the load pipeline of
+ *                                 the parallel-reduction kernels (next block requested behind this block's gathers)
+ *   DGSP_PROBE_ROW_GATHER         N a multiple of 4: entries staged in LDS 512 at a time, lane groups walk them
+ *                                 and load 16 bytes of the entry's row of X per lane (64 columns per group at most,
+ *                                 further columns as further blocks): the walk of the sequential-reduction
+ *                                 kernels without rows
+ * colidx, vals: device, nnz entries, 0 <= colidx < K.  X: device, fp32 K x N row-major, ld = N.  out: device,
+ * dgsp_floor_probe_out_len(mode, N) floats (-1: mode / N not offered), overwritten with the per-thread partial
+ * sums: their total equals the sum over all entries p and columns n of vals[p] * X[colidx[p], n] (for
+ * DGSP_PROBE_GATHER: of X[colidx[p]]), which is also the sum of all elements of A X.
+ * Errors: DGSP_ERR_UNSUPPORTED for an N the mode does not offer, DGSP_ERR_INVALID_ARG otherwise.
+ */
+typedef enum { DGSP_PROBE_GATHER = 0, DGSP_PROBE_STREAM_GATHER_FMA = 1, DGSP_PROBE_ROW_GATHER = 2 } dgsp_probe_mode_t;
+int dgsp_floor_probe(int mode, int64_t nnz, int64_t K, int64_t N, const int32_t *colidx, const float *vals,
+                     const float *X, float *out, void *stream);
+int64_t dgsp_floor_probe_out_len(int mode, int64_t N);
 
 /*
  * Measurement aid, not part of the method: dst[i] = src[i] for i < n (device

@@ -24,10 +24,12 @@ EXPORTS = (
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
     "dgsp_spmm_csr_ablation", "dgsp_features_from_csr_device", "dgsp_autotune",
     "dgsp_spmm_csr_ld", "dgsp_spmm_csr_axpby", "dgsp_features_from_csr_device_noalloc",
+    "dgsp_floor_probe", "dgsp_floor_probe_out_len",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
-ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING = 1, 2
+ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING, ABL_ITEM_TILES = 1, 2, 4
 FEATURES_WORKSPACE_BYTES = 64
+PROBE_GATHER, PROBE_STREAM_GATHER_FMA, PROBE_ROW_GATHER = 0, 1, 2
 
 
 class Features(ctypes.Structure):
@@ -104,6 +106,10 @@ def lib():
         L.dgsp_gather_probe.argtypes = [vp, vp, vp, i64, vp]
         L.dgsp_gather_probe_out_len.restype = i64
         L.dgsp_gather_probe_out_len.argtypes = []
+        L.dgsp_floor_probe.restype = ci
+        L.dgsp_floor_probe.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, vp]
+        L.dgsp_floor_probe_out_len.restype = i64
+        L.dgsp_floor_probe_out_len.argtypes = [ci, i64]
         L.dgsp_copy_f32.restype = ci
         L.dgsp_copy_f32.argtypes = [vp, vp, i64, vp]
         L.dgsp_algo_name.restype = ctypes.c_char_p
@@ -254,6 +260,20 @@ def dgsp_gather_probe(out, x, idx, n=None, stream=None):
         raise DgspError("out is shorter than dgsp_gather_probe_out_len()")
     rc = lib().dgsp_gather_probe(_ptr(out), _ptr(x), _ptr(idx), int(n), _stream(stream))
     _check(rc, "dgsp_gather_probe")
+
+
+def dgsp_floor_probe_out_len(mode, N) -> int:
+    return int(lib().dgsp_floor_probe_out_len(int(mode), int(N)))
+
+
+def dgsp_floor_probe(mode, K, N, colidx, vals, X, out, stream=None):
+    """The memory side of the kernels with no row logic (measurement aid); ``out`` receives per-thread partial sums
+    whose total is the sum of all elements of ``A X``."""
+    if out.numel() < dgsp_floor_probe_out_len(mode, N):
+        raise DgspError("out is shorter than dgsp_floor_probe_out_len(mode, N) (or the mode does not offer this N)")
+    rc = lib().dgsp_floor_probe(int(mode), int(colidx.numel()), int(K), int(N), _ptr(colidx), _ptr(vals), _ptr(X),
+                                _ptr(out), _stream(stream))
+    _check(rc, "dgsp_floor_probe")
 
 
 def dgsp_gather_probe_out_len() -> int:

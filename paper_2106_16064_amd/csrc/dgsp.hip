@@ -306,6 +306,13 @@ int launch_prepare(const Problem& p, unsigned parts, unsigned quantum_log2, int 
 //     that nothing overlaps yet) and fewer waves leave more of the L1 to each - but two as soon as
 //     that leaves a wave 6 tiles (measured on matrices of 1 M to 57 M entries).
 constexpr long long kNbPrTilesPerWave = 12;
+#ifndef DGSP_X_KQ
+#define DGSP_X_KQ 2
+#endif
+#ifndef DGSP_X_PRCU
+#define DGSP_X_PRCU 0
+#endif
+constexpr int kNbPrKq = DGSP_X_KQ;          // quads of entries per lane and tile in the balanced parallel kernel (V <= 4)
 
 inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per_cu, bool parallel,
                                 long long col_blocks = 1) {
@@ -320,7 +327,7 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
     if (parallel) {
         per_cu = tiles / (waves * kNbPrTilesPerWave);
         if (per_cu < 2) per_cu = tiles >= waves * kNbPrTilesPerWave ? 2 : 1;
-
+        if (DGSP_X_PRCU > 0) per_cu = DGSP_X_PRCU;
     } else {
         // the column blocks of a wide X (grid.y) are resident side by side: count them in
         const long long want = (tiles * col_blocks + waves - 1) / waves;
@@ -331,21 +338,41 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
     return (unsigned)(cus * per_cu);
 }
 
+// Which pipeline the balanced parallel kernel runs.  Blocks of entries with the next block's gathers in flight
+// during the row logic (nb_pr_kernel) for one or two dense columns per lane: 8-9 % faster on power-law rows
+// (R-MAT 2^20: 98 -> 90 us at N = 1), even on the 27-point stencil.  From three columns on the registers that hold
+// a block's gathered values halve the resident waves (176 VGPRs at V = 4), which costs more than the overlap
+// gives (stencil N = 4: 150 -> 201 us), so those widths keep the tiles of merge-path items (nb_pr_tiled_kernel).
+// DGSP_ABL_ITEM_TILES forces the tiled pipeline everywhere (the comparison for this choice).
+template <int V>
+constexpr bool kNbPrStreams = V <= 2;
+
 template <int V, int KQ>
 int launch_nb_pr_v(const Problem& p) {
     constexpr unsigned tile = kWave * 4 * KQ;
     const unsigned col_groups = (unsigned)((p.N + V - 1) / V);      // V = 8 also takes N = 5, 6, 7: one group
-    // the row store addresses a tile's rows with 32-bit byte offsets: tile rows * N * 4 must fit
+    // the row store addresses a step's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
-    const dim3 grid(balanced_blocks(p, tile, resident_blocks_per_cu(nb_pr_kernel<V, KQ>), true), col_groups);
+    const bool tiled = !kNbPrStreams<V> || (p.switches & DGSP_ABL_ITEM_TILES) != 0;
+    int resident = resident_blocks_per_cu(nb_pr_tiled_kernel<V, KQ>);
+    if constexpr (kNbPrStreams<V>) { if (!tiled) resident = resident_blocks_per_cu(nb_pr_kernel<V, KQ>); }
+    const dim3 grid(balanced_blocks(p, tile, resident, true), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
-        if (p.scaled)
-            DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
-                        Scaling{p.alpha, p.beta});
-        else
-            DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+        if (tiled) {
+            if (p.scaled)
+                DGSP_LAUNCH((nb_pr_tiled_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X,
+                            p.Y, Scaling{p.alpha, p.beta});
+            else
+                DGSP_LAUNCH((nb_pr_tiled_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+        } else if constexpr (kNbPrStreams<V>) {
+            if (p.scaled)
+                DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
+                            Scaling{p.alpha, p.beta});
+            else
+                DGSP_LAUNCH((nb_pr_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+        }
     }
     return DGSP_OK;
 }
@@ -358,10 +385,10 @@ int launch_nb_pr(const Problem& p) {
     if (p.N >= 5 && p.N <= 7 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
         return launch_nb_pr_v<8, 1>(p);
     switch (pr_vector_width(p)) {
-        case 4: return launch_nb_pr_v<4, 2>(p);
-        case 3: return launch_nb_pr_v<3, 2>(p);
-        case 2: return launch_nb_pr_v<2, 2>(p);
-        default: return launch_nb_pr_v<1, 2>(p);
+        case 4: return launch_nb_pr_v<4, kNbPrKq>(p);
+        case 3: return launch_nb_pr_v<3, kNbPrKq>(p);
+        case 2: return launch_nb_pr_v<2, kNbPrKq>(p);
+        default: return launch_nb_pr_v<1, kNbPrKq>(p);
     }
 }
 
@@ -529,8 +556,9 @@ extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t n
                                       const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
                                       int switches, const dgsp_features_t* features, void* stream) {
     if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
-    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING)) return DGSP_ERR_INVALID_ARG;
+    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING | DGSP_ABL_ITEM_TILES)) return DGSP_ERR_INVALID_ARG;
     if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
+    if ((switches & DGSP_ABL_ITEM_TILES) && algo != DGSP_NB_PR) return DGSP_ERR_UNSUPPORTED;
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                Hints(features), switches);
@@ -617,6 +645,65 @@ extern "C" int dgsp_gather_probe(float* out, const float* x, const int32_t* idx,
     hipLaunchKernelGGL(gather_probe_kernel, dim3(kGatherProbeBlocks), dim3(kBlock), 0, (hipStream_t)stream, out, x,
                        idx, (long long)n);
     return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
+}
+
+// ---------------------------------------------------------------- floor probes (measurement aids)
+namespace {
+#ifndef DGSP_X_PROBE_BLOCKS
+#define DGSP_X_PROBE_BLOCKS 1024
+#endif
+constexpr int kStreamProbeBlocks = DGSP_X_PROBE_BLOCKS;        // four workgroups per CU: what the lean pipeline ran best with
+
+struct RowProbeShape { int logG; unsigned col_blocks; unsigned blocks; };
+RowProbeShape row_probe_shape(int64_t N) {
+    const int logG = sr_lanes_log2(N, 4, 4);                               // at most 16 lanes = 64 columns per group
+    const unsigned col_blocks = (unsigned)((N + (4 << logG) - 1) / (4 << logG));
+    const unsigned blocks = (unsigned)(device_info().cus * resident_blocks_per_cu(row_gather_probe_kernel));
+    return {logG, col_blocks, blocks};
+}
+}  // namespace
+
+extern "C" int64_t dgsp_floor_probe_out_len(int mode, int64_t N) {
+    if (mode == DGSP_PROBE_GATHER) return dgsp_gather_probe_out_len();
+    if (mode == DGSP_PROBE_STREAM_GATHER_FMA) return (N == 1 || N == 2 || N == 4) ? (int64_t)kStreamProbeBlocks * kBlock * N : -1;
+    if (mode == DGSP_PROBE_ROW_GATHER) {
+        if (N < 4 || N % 4 != 0) return -1;
+        const RowProbeShape sh = row_probe_shape(N);
+        return (int64_t)sh.blocks * sh.col_blocks * kBlock * 4;
+    }
+    return -1;
+}
+
+extern "C" int dgsp_floor_probe(int mode, int64_t nnz, int64_t K, int64_t N, const int32_t* colidx, const float* vals,
+                                const float* X, float* out, void* stream) {
+    if (nnz < 0 || K < 1 || N < 1 || !out || !X || (nnz > 0 && !colidx)) return DGSP_ERR_INVALID_ARG;
+    const int64_t lim = (int64_t)INT32_MAX - 4096;
+    if (nnz > lim || K > lim || N > (1 << 20)) return DGSP_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (mode == DGSP_PROBE_GATHER) {
+        if (N != 1) return DGSP_ERR_UNSUPPORTED;
+        return dgsp_gather_probe(out, X, colidx, nnz, stream);
+    }
+    if (nnz > 0 && !vals) return DGSP_ERR_INVALID_ARG;
+    if (mode == DGSP_PROBE_STREAM_GATHER_FMA) {
+        const dim3 grid(kStreamProbeBlocks);
+        switch (N) {
+            case 1: hipLaunchKernelGGL(stream_gather_fma_probe_kernel<1>, grid, dim3(kBlock), 0, st, out, X, (long long)K, 1, colidx, vals, (long long)nnz); break;
+            case 2: hipLaunchKernelGGL(stream_gather_fma_probe_kernel<2>, grid, dim3(kBlock), 0, st, out, X, (long long)K, 2, colidx, vals, (long long)nnz); break;
+            case 4: hipLaunchKernelGGL(stream_gather_fma_probe_kernel<4>, grid, dim3(kBlock), 0, st, out, X, (long long)K, 4, colidx, vals, (long long)nnz); break;
+            default: return DGSP_ERR_UNSUPPORTED;
+        }
+        return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
+    }
+    if (mode == DGSP_PROBE_ROW_GATHER) {
+        if (N < 4 || N % 4 != 0) return DGSP_ERR_UNSUPPORTED;
+        const RowProbeShape sh = row_probe_shape(N);
+        if (sh.col_blocks > 65535u) return DGSP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(row_gather_probe_kernel, dim3(sh.blocks, sh.col_blocks), dim3(kBlock), 0, st, out, X, (long long)K,
+                           (int)N, (int)N, colidx, vals, (long long)nnz, sh.logG);
+        return hipGetLastError() == hipSuccess ? DGSP_OK : DGSP_ERR_LAUNCH;
+    }
+    return DGSP_ERR_INVALID_ARG;
 }
 
 extern "C" int dgsp_features_from_csr_host(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colidx,

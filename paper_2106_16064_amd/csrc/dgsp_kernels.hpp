@@ -500,7 +500,7 @@ constexpr unsigned kNoRow = 0xffffffffu;
 // blockIdx.y selects the group of V dense columns (N > V: one pass each).
 
 template <int V, int KQ, bool AXPBY = false>
-__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) void nb_pr_tiled_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
@@ -780,6 +780,377 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     }
 
     store_pending();                                       // the last tile's rows
+    // the row still open at the end of my chunk is finished by another wave
+    bool any = false;
+#pragma unroll
+    for (int i = 0; i < V; ++i) any |= carry[i] != 0.0f;
+    if constexpr (AXPBY) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) carry[i] *= sc.alpha;
+    }
+    if (any && lane == 0 && is < M) add_to_row(Y + (size_t)is * ldy + n0, carry);
+    }   // next chunk
+}
+
+// ===========================================================================
+// nnz-balanced, parallel reduction with the entry stream decoupled from the rows
+// ===========================================================================
+//
+// The kernel above cuts a chunk into tiles of W merge-path items, so where the entries of tile t + 1 begin is
+// known only when the row ends of tile t have been counted: its gathers cannot be requested before the row
+// logic of tile t is through, and a wave spends that logic with no gather in flight.  Here the chunk (still an
+// equal share of merge-path items, found by two 64-way searches in lock-step) is walked in BLOCKS of W consecutive
+// ENTRIES counted from the chunk's first entry, so every block's address is known from the start:
+//   * everything a block needs from memory is requested one block ahead: while the rows of block k are finished,
+//     the gathers of block k + 1 and the entries of block k + 2 are in flight (the entries land in registers of
+//     their own and are moved when they have arrived, so the loop needs no unrolling);
+//   * the products of a block change hands through LDS as before (lane l ends up with E consecutive products)
+//     and stay in registers while the rows that end inside the block are finished in STEPS: a step takes up to W
+//     row ends (the LDS marks and the staged row results are sized for that) and the entries up to the end of the
+//     last of them, or up to the block's end when fewer than W rows end in the block - the usual case, one step
+//     per block.  A stretch of empty rows simply takes more steps; entries outside the step's range are masked;
+//   * per step everything else is the scheme of the kernel above: row-end marks in LDS, in-lane sums of E
+//     consecutive products, one segmented DPP scan over the lanes' open-row partials (Section 2.1.1), results
+//     staged by row and stored 64 rows at a time, the open row's sum carried in a register.
+// The row-bound window of the next step is requested before the next entries, so waiting for it does not wait
+// for them (loads return in issue order).
+
+// Rows that ended before diagonal da, and before db (both searches of wave_merge_rows_before in lock-step: their
+// probes are in flight together, so the second costs no further round trips).
+__device__ __forceinline__ void wave_merge_rows_before2(const int* __restrict__ rowptr, int M, unsigned da, unsigned db,
+                                                        int lane, int& ra, int& rb) {
+    int lo[2] = {0, 0}, hi[2] = {M, M};
+    const unsigned d[2] = {da, db};
+    while (hi[0] > lo[0] || hi[1] > lo[1]) {
+        int step[2], v[2];
+        long long r[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            step[k] = (hi[k] - lo[k] + 63) >> 6;
+            r[k] = (long long)lo[k] + (long long)lane * step[k];
+            v[k] = (hi[k] > lo[k] && r[k] < hi[k]) ? rowptr[r[k] + 1] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (hi[k] > lo[k]) {                                   // wave-uniform
+                const bool before = r[k] < hi[k] && (unsigned)r[k] + (unsigned)v[k] < d[k];
+                const int cnt = __popcll(__ballot(before));       // probes are monotone: 1...10...0
+                if (cnt == 0) {
+                    hi[k] = lo[k];
+                } else {
+                    const int nlo = lo[k] + (cnt - 1) * step[k] + 1;
+                    const int nhi = lo[k] + cnt * step[k];
+                    lo[k] = nlo;
+                    hi[k] = nhi < hi[k] ? nhi : hi[k];
+                }
+            }
+        }
+    }
+    ra = uniform(lo[0]);
+    rb = uniform(lo[1]);
+}
+
+template <int V, int KQ, bool AXPBY = false>
+__global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
+                                                        const int* __restrict__ colidx,
+                                                        const float* __restrict__ vals,
+                                                        const float* __restrict__ X, float* __restrict__ Y,
+                                                        Scaling sc = Scaling{1.0f, 0.0f}) {
+    constexpr int E = 4 * KQ;
+    constexpr int W = kWave * E;
+    __shared__ __align__(16) unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the step's first entry
+    __shared__ __align__(16) float s_buf[kWavesPerBlock][W * V];      // products, then a step's row results
+    const int lane = lane_id();
+    const int wib = wave_in_block();
+    unsigned* bnd = s_bnd[wib];
+    float* buf = s_buf[wib];
+    const int n0 = blockIdx.y * V;
+
+    const ChunkPlan plan = plan_chunks(rowptr, M, 6);        // quanta of one wave's width
+    const unsigned nnz = plan.nnz;
+    const unsigned long long y_elems = dense_bytes(M, ldy, N) / 4ull;
+    // V = 8: the lane's second four columns start here (N = 5, 6, 7: at N - 4, overlapping the first four)
+    const int second = (V == 8 && N - n0 < 8) ? N - n0 - 4 : 4;
+
+    auto add_to_row = [&](float* y, const float (&v)[V]) {
+        if constexpr (V == 8) atomic_add_halves(y, v, second); else atomic_add_vec<V>(y, v);
+    };
+
+    for (unsigned sub = 0; sub < kSubRanges; ++sub) {
+    unsigned d0, d1;
+    if (!plan.range(sub, d0, d1)) continue;
+
+    if (nnz == 0) {
+        // nothing stored: every item is a row end; my rows are [d0, d1)
+        for (unsigned r = d0 + lane; r < d1; r += kWave) {
+            float* y = Y + (size_t)r * ldy + n0;
+            float out[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) out[i] = 0.0f;
+            if constexpr (AXPBY) scale_into<V, true>(out, y, sc, second);
+            store_vec_dword_aligned<V>(y, out, second);
+        }
+        continue;
+    }
+
+    // my chunk: rows [is, ie1) end in it, entries [js0, je1) lie in it
+    int is, ie1;
+    wave_merge_rows_before2(rowptr, M, d0, d1, lane, is, ie1);
+    const unsigned js0 = d0 - (unsigned)is;
+    const unsigned je1 = d1 - (unsigned)ie1;
+    unsigned js = js0;
+    // the first row to end in my chunk started before it?  then its sum is shared with another wave
+    const int r_first = is;
+    const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < d0;
+
+    // entries of block k of my chunk (lane l: entries 64 e + l of the block); nothing past the chunk's last entry
+    auto load_entries = [&](unsigned k, int (&c)[E], float (&a)[E]) {
+        const unsigned long long from = (unsigned long long)js0 + (unsigned long long)k * W;
+        const unsigned long long bytes = from < je1 ? ((unsigned long long)je1 - from) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + (bytes ? from : 0ull), bytes);
+        const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + (bytes ? from : 0ull), bytes);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const unsigned off = (unsigned)(e * kWave + lane) * 4u;
+            c[e] = (int)__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 2);
+            a[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra, off, 0, 2));
+        }
+    };
+    // the dense operand: byte offsets of X rows fit 32 bits unless X is 4 GB or more
+    const unsigned long long x_bytes = dense_bytes(K, ldx, N);
+    const bool x_small = x_bytes <= 0xffffffffull;
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
+    // one vector gather per entry of block k, from the columns that load_entries(k) brought
+    auto gather = [&](unsigned k, const int (&c)[E], float (&x)[E][V]) {
+        const unsigned long long from = (unsigned long long)js0 + (unsigned long long)k * W;
+        const int left = from < je1 ? (int)((unsigned long long)je1 - from < (unsigned long long)W ? (unsigned long long)je1 - from : (unsigned long long)W) : 0;
+        if (x_small) {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                buffer_load_vec<V>(rx, e * kWave + lane < left ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e], second);
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                load_vec_dword_aligned<V>(X + (size_t)(e * kWave + lane < left ? c[e] : 0) * ldx + n0, x[e], second);
+        }
+    };
+    // end offset of row `first + lane` (rows past the last one read as 0)
+    auto load_row_ends = [&](int first, bool on, unsigned& end) {
+        const unsigned long long bytes = (on && first < M) ? (unsigned long long)(M + 1 - first) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t rr = make_buffer(rowptr + (bytes ? first : 0), bytes);
+        end = __builtin_amdgcn_raw_buffer_load_b32(rr, (unsigned)(lane + 1) * 4u, 0, 0);
+    };
+
+    float carry[V];      // running sum of the row that is open at the step boundary (wave-uniform)
+#pragma unroll
+    for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+
+    // The first 64 row results of a step are stored one step later, behind the loads issued meanwhile (the memory
+    // pipeline retires loads and stores in issue order: a store in front of the gathers adds its round trip to their wait).
+    float pending_val[V];
+    unsigned pending_off = kOutOfRange;
+    unsigned long long pending_first = 0ull;             // first element of the rows the pending store addresses
+#pragma unroll
+    for (int i = 0; i < V; ++i) pending_val[i] = 0.0f;
+    auto rows_descriptor = [&](unsigned long long first_elem) {
+        const unsigned long long left = first_elem < y_elems ? (y_elems - first_elem) * 4ull : 0ull;
+        return __builtin_amdgcn_make_buffer_rsrc((void*)(Y + first_elem), 0, left > 0xffffffffull ? 0xffffffffu : (unsigned)left,
+                                                 kBufferFlags);
+    };
+    auto store_pending = [&]() {
+        buffer_store_vec<V>(rows_descriptor(pending_first), pending_off, pending_val, second);
+        pending_off = kOutOfRange;
+    };
+
+    int c[E]; float a[E], x[E][V];                        // the block whose gathers are in flight
+    int lc[E]; float la[E];                               // landing registers of the next block's entries
+    unsigned w_end;                                       // end offsets of rows is .. is + 63 (lane l: row is + l)
+    load_entries(0, lc, la);
+    load_row_ends(is, is < ie1, w_end);
+#pragma unroll
+    for (int e = 0; e < E; ++e) { c[e] = lc[e]; a[e] = la[e]; }
+    load_entries(1, lc, la);
+    gather(0, c, x);
+
+    // state of the step in flight between its two halves
+    int ie = is, nrows = 0;
+    unsigned je = js, blk_start = js0, blk_end = js0;
+    bool capped = false;
+
+    // first half of a step: which rows end in it, their marks, the next step's row window
+    auto step_rows = [&]() {
+        wave_lds_sync();                                   // the previous step's readers are done
+#pragma unroll
+        for (int k = 0; k < KQ; ++k)
+            *reinterpret_cast<uint4*>(bnd + E * lane + 4 * k) = make_uint4(kNoRow, kNoRow, kNoRow, kNoRow);
+        if (lane == 0) bnd[W] = kNoRow;
+        wave_lds_sync();
+        const unsigned js_l = js - blk_start;              // the step's first entry, counted from the block's start
+        ie = is;
+        // marks the rows of one batch of 64 candidates that end in this block (and in my chunk); returns how many did
+        auto mark_row_ends = [&](int m, unsigned end) {
+            const long long r = (long long)is + m * kWave + lane;
+            const bool ends = r < ie1 && end <= blk_end;
+            if (ends) {
+                const unsigned q = end - blk_start;        // it ends after entry q-1 of the block; q >= js_l
+                atomicMin(bnd + (q > js_l ? q - 1 : (unsigned)W), (unsigned)(r - is));
+            }
+            return (int)__popcll(__ballot(ends));
+        };
+        int cnt = mark_row_ends(0, w_end);                 // the first 64 candidates were loaded a step ago
+        ie += cnt;
+        unsigned last_end = 0;
+        if (cnt == kWave) {
+            // crowded with row ends: fetch all remaining candidates of the step at once
+            unsigned me[E - 1];
+#pragma unroll
+            for (int m = 1; m < E; ++m) load_row_ends(is + m * kWave, true, me[m - 1]);
+#pragma unroll
+            for (int m = 1; m < E; ++m) {
+                if (cnt == kWave) { cnt = mark_row_ends(m, me[m - 1]); ie += cnt; }
+            }
+            last_end = (unsigned)read_lane((int)me[E - 2], kWave - 1);      // end of row is + W - 1
+        }
+        nrows = ie - is;
+        capped = nrows == W;                               // more rows may end in this block: another step
+        je = capped ? last_end : blk_end;                  // capped: up to the end of the last row taken
+        load_row_ends(ie, ie < ie1, w_end);                // candidates of the next step
+    };
+
+    // second half: reduce the step's entries, finish its rows
+    auto step_sums = [&](const float (&pr)[E][V]) {
+        store_pending();                                   // the previous step's rows
+        wave_lds_sync();                                   // marks are in place
+        const int js_l = (int)(js - blk_start), je_l = (int)(je - blk_start);
+        const unsigned b_in = bnd[W];
+        unsigned b[E];
+#pragma unroll
+        for (int k = 0; k < KQ; ++k) {
+            const uint4 t = *reinterpret_cast<const uint4*>(bnd + E * lane + 4 * k);
+            b[4 * k] = t.x; b[4 * k + 1] = t.y; b[4 * k + 2] = t.z; b[4 * k + 3] = t.w;
+        }
+        // ---- the step's row results: cleared, so rows without entries come out as zeros
+        for (int k = 0; k * kWave < nrows; ++k) {
+            float zero[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) zero[i] = 0.0f;
+            store_vec<V>(buf + (size_t)(k * kWave + lane) * V, zero);
+        }
+        wave_lds_sync();
+        // rows that end before the step's first entry take the sum carried in
+        if (b_in != kNoRow) {
+            if (lane == 0) store_vec<V>(buf + (size_t)b_in * V, carry);
+#pragma unroll
+            for (int i = 0; i < V; ++i) carry[i] = 0.0f;
+        }
+
+        // ---- in-lane reduction over my E consecutive entries (those of this step)
+        float s[V], head[V];
+        unsigned head_row = kNoRow;                        // kNoRow: no boundary inside this lane
+#pragma unroll
+        for (int i = 0; i < V; ++i) { s[i] = lane == 0 ? carry[i] : 0.0f; head[i] = 0.0f; }
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int pos = E * lane + e;
+            const bool in = pos >= js_l && pos < je_l;
+#pragma unroll
+            for (int i = 0; i < V; ++i) s[i] += in ? pr[e][i] : 0.0f;
+            if (b[e] != kNoRow) {
+                if (head_row == kNoRow) {
+                    head_row = b[e];
+#pragma unroll
+                    for (int i = 0; i < V; ++i) head[i] = s[i];
+                } else {
+                    store_vec<V>(buf + (size_t)b[e] * V, s);   // a row that begins and ends inside this lane
+                }
+#pragma unroll
+                for (int i = 0; i < V; ++i) s[i] = 0.0f;
+            }
+        }
+
+        // ---- the open row across lanes: segments start at lanes that hold a boundary
+        const bool flagged = head_row != kNoRow;
+        const int head_lane = (int)wave_max_scan(flagged ? (unsigned)lane : 0u);
+        segmented_scan<V>(s, lane - head_lane, lane);      // s: sum of the open row up to and including my lane
+        {
+            float closing[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) closing[i] = dpp_or_zero<kDppWaveShr1, 0xf>(s[i]) + head[i];
+            if (flagged) store_vec<V>(buf + (size_t)head_row * V, closing);
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) carry[i] = read_lane(s[i], kWave - 1);
+        wave_lds_sync();
+
+        // ---- write the rows [is, ie) out, lane l row is + l: the first 64 with one unconditional
+        //      buffer store (issued a step later), further batches in a loop
+        {
+            const unsigned long long first_elem = (unsigned long long)is * (unsigned)ldy + (unsigned)n0;
+            __amdgpu_buffer_rsrc_t yrows = rows_descriptor(first_elem);
+            auto write_rows = [&](int k) {
+                const int t = k * kWave + lane;                     // local row
+                float val[V];
+                load_vec<V>(buf + (size_t)t * V, val);
+                const bool live = t < nrows;
+                const bool shared = first_split && is + t == r_first;   // finished by an atomic add instead
+                const unsigned off = (live && !shared) ? (unsigned)t * (unsigned)ldy * 4u : kOutOfRange;
+                if constexpr (AXPBY) {
+                    if (live && shared) {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) val[i] *= sc.alpha;          // lands on beta * Y (prepare)
+                    } else {
+                        scale_into<V>(val, yrows, off, sc, second);
+                    }
+                }
+                if (k == 0) {
+                    pending_first = first_elem; pending_off = off;
+#pragma unroll
+                    for (int i = 0; i < V; ++i) pending_val[i] = val[i];
+                } else {
+                    buffer_store_vec<V>(yrows, off, val, second);
+                }
+                if (live && shared) add_to_row(Y + (size_t)(is + t) * ldy + n0, val);
+            };
+            write_rows(0);
+            for (int k = 1; k * kWave < nrows; ++k) write_rows(k);
+        }
+        is = ie;
+        js = je;
+    };
+
+    const unsigned nblocks = (je1 - js0 + (unsigned)W - 1) / (unsigned)W;
+    const unsigned nb = nblocks ? nblocks : 1u;            // a chunk without entries still has its row ends to finish
+    for (unsigned k = 0; k < nb; ++k) {
+        blk_start = js0 + k * (unsigned)W;                 // == js: the previous block was consumed to its end
+        blk_end = (je1 - blk_start > (unsigned)W) ? blk_start + (unsigned)W : je1;
+        // ---- products of block k change hands through LDS: entry 64e+l of the block -> lane (64e+l)/E
+        const int nE = (int)(blk_end - blk_start);
+        wave_lds_sync();                                   // the previous step's readers of the buffer are done
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float p[V];
+            const bool mine = e * kWave + lane < nE;
+#pragma unroll
+            for (int i = 0; i < V; ++i) p[i] = mine ? a[e] * x[e][i] : 0.0f;
+            store_vec<V>(buf + (size_t)(e * kWave + lane) * V, p);
+        }
+        wave_lds_sync();
+        float pr[E][V];
+#pragma unroll
+        for (int e = 0; e < E; ++e) load_vec<V>(buf + (size_t)(E * lane + e) * V, pr[e]);
+        // ---- block k + 1's entries have landed: request its gathers and block k + 2's entries; both stay in
+        //      flight while the rows of block k are finished
+#pragma unroll
+        for (int e = 0; e < E; ++e) { c[e] = lc[e]; a[e] = la[e]; }
+        load_entries(k + 2, lc, la);
+        gather(k + 1, c, x);
+        do {                                               // one step, unless more than W rows end in this block
+            step_rows();
+            step_sums(pr);                                 // (its first LDS fence also frees the product buffer)
+        } while (capped);
+    }
+
+    store_pending();                                       // the last step's rows
     // the row still open at the end of my chunk is finished by another wave
     bool any = false;
 #pragma unroll
@@ -1199,7 +1570,7 @@ __global__ __launch_bounds__(kBlock) void features_kernel(int M, const int* __re
 }
 
 // ===========================================================================
-// measurement aids: pure gather, plain streaming copy
+// measurement aids: pure gather, the memory side of the parallel and of the sequential kernels, plain streaming copy
 // ===========================================================================
 
 // Streams idx and gathers x[idx[i]], four independent gathers in flight per
@@ -1220,6 +1591,134 @@ __global__ __launch_bounds__(kBlock) void gather_probe_kernel(float* __restrict_
         for (int u = 0; u < 4; ++u) acc += c[u] >= 0 ? x[c[u]] : 0.0f;
     }
     out[t] = acc;
+}
+
+// Floor of the parallel-reduction kernels: what they do to memory and nothing else.  A wave takes blocks of
+// 512 consecutive entries; lane l loads entries 64 e + l (coalesced, non-temporal), gathers V dense values for
+// each with one vector load and multiplies-adds them into V private sums.  Three register sets rotate: while
+// block b is multiplied, the gathers of block b + 1 and the entries of block b + 2 are in flight, and the
+// entries of block b + 3 are requested as soon as block b's registers are free.  No row bounds, no reduction
+// across lanes, no result rows: the per-lane sums go to out[thread * V + i] so that the loads stay alive (and so
+// that a test can check their total).
+template <int V>
+__global__ __launch_bounds__(kBlock) void stream_gather_fma_probe_kernel(float* __restrict__ out, const float* __restrict__ X,
+                                                                         long long K, int ldx, const int* __restrict__ colidx,
+                                                                         const float* __restrict__ vals, long long nnz) {
+#ifndef DGSP_X_PROBE_E
+#define DGSP_X_PROBE_E 8
+#endif
+    constexpr int E = DGSP_X_PROBE_E;
+    constexpr long long W = kWave * E;
+    const int lane = lane_id();
+    const long long nwaves = (long long)gridDim.x * kWavesPerBlock;
+    const long long gw = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block();
+    const long long nblocks = (nnz + W - 1) / W;
+    const long long b0 = nblocks * gw / nwaves, b1 = nblocks * (gw + 1) / nwaves;      // my contiguous share
+    const unsigned long long x_bytes = dense_bytes(K, ldx, V);
+    const bool x_small = x_bytes <= 0xffffffffull;
+    const __amdgpu_buffer_rsrc_t rx = make_buffer(X, x_small ? x_bytes : 0ull);
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+    struct Set { int c[E]; float a[E]; float x[E][V]; };
+    // entries of block b (nothing past my share or past the arrays' end: zeros, which add nothing)
+    auto load_entries = [&](long long b, Set& s) {
+        const long long from = b * W;
+        const unsigned long long bytes = (b < b1 && from < nnz) ? (unsigned long long)(nnz - from) * 4ull : 0ull;
+        const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + (bytes ? from : 0), bytes);
+        const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + (bytes ? from : 0), bytes);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const unsigned off = (unsigned)(e * kWave + lane) * 4u;
+            s.c[e] = buffer_stream_i32(rc, off);
+            s.a[e] = buffer_stream_f32(ra, off);
+        }
+    };
+    auto gather = [&](long long b, Set& s) {
+        const long long left = b < b1 ? nnz - b * W : 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const bool ok = e * kWave + lane < left;
+            if (x_small) {
+                buffer_load_vec<V>(rx, ok ? (unsigned)s.c[e] * (unsigned)ldx * 4u : kOutOfRange, s.x[e]);
+            } else {
+                load_vec_dword_aligned<V>(X + (size_t)(ok ? s.c[e] : 0) * ldx, s.x[e]);
+            }
+        }
+    };
+    // one step: s0 holds block b (gathers in flight), s1 block b + 1 (entries arrived), s2 block b + 2 (in flight)
+    auto step = [&](long long b, Set& s0, Set& s1) {
+        gather(b + 1, s1);
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(s0.a[e], s0.x[e][i], acc[i]);
+        load_entries(b + 3, s0);
+    };
+    Set s0, s1, s2;
+    load_entries(b0, s0);
+    load_entries(b0 + 1, s1);
+    load_entries(b0 + 2, s2);
+    gather(b0, s0);
+    for (long long b = b0; b < b1; b += 3) {
+        step(b, s0, s1);
+        if (b + 1 < b1) step(b + 1, s1, s2);
+        if (b + 2 < b1) step(b + 2, s2, s0);
+    }
+    const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < V; ++i) out[t * V + i] = acc[i];
+}
+
+// Floor of the sequential-reduction kernels at width N: a wave stages 512 consecutive entries in LDS with
+// coalesced loads, then each of its 64 / G lane groups walks 512 G / 64 of them in order, one dwordx4 load of the
+// entry's row of X per lane and step (lane gl owns columns [block * 4 G + 4 gl, + 4)), multiply-add into four private
+// sums.  No rows, no stores inside the walk.  blockIdx.y selects the block of 4 G columns.  N must be a multiple of 4.
+__global__ __launch_bounds__(kBlock) void row_gather_probe_kernel(float* __restrict__ out, const float* __restrict__ X,
+                                                                  long long K, int N, int ldx, const int* __restrict__ colidx,
+                                                                  const float* __restrict__ vals, long long nnz, int logG) {
+    constexpr int W = 512;
+    __shared__ __align__(16) int s_col[kWavesPerBlock][W];
+    __shared__ __align__(16) float s_val[kWavesPerBlock][W];
+    const int lane = lane_id();
+    const int wib = wave_in_block();
+    int* cc = s_col[wib];
+    float* cv = s_val[wib];
+    const int G = 1 << logG;
+    const int gl = lane & (G - 1), g = lane >> logG;
+    const int U = W >> (6 - logG);                                   // entries per group and tile
+    const long long n = (long long)blockIdx.y * 4 * G + 4 * gl;      // my first column
+    const bool col_ok = n + 4 <= N;
+    const long long nwaves = (long long)gridDim.x * kWavesPerBlock;
+    const long long gw = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wib;
+    const long long ntiles = (nnz + W - 1) / W;
+    const long long t0 = ntiles * gw / nwaves, t1 = ntiles * (gw + 1) / nwaves;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (long long t = t0; t < t1; ++t) {
+        const long long from = t * W;
+        const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + from, (unsigned long long)(nnz - from) * 4ull);
+        const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + from, (unsigned long long)(nnz - from) * 4ull);
+        wave_lds_sync();
+#pragma unroll
+        for (int k = 0; k < W / kWave; ++k) {
+            const int e = k * kWave + lane;
+            cc[e] = buffer_stream_i32(rc, (unsigned)e * 4u);      // past the end: column 0, value 0
+            cv[e] = buffer_stream_f32(ra, (unsigned)e * 4u);
+        }
+        wave_lds_sync();
+        if (col_ok) {
+            for (int e = g * U; e < (g + 1) * U; ++e) {
+                float x[4];
+                load_vec_dword_aligned<4>(X + (size_t)cc[e] * ldx + n, x);
+                const float a = cv[e];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = fmaf(a, x[i], acc[i]);
+            }
+        }
+    }
+    const long long th = ((long long)blockIdx.y * gridDim.x + blockIdx.x) * kBlock + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[th * 4 + i] = acc[i];
 }
 
 __global__ __launch_bounds__(kBlock) void copy_kernel(float* __restrict__ dst, const float* __restrict__ src,

@@ -304,6 +304,45 @@ def test_gather_probe_sums_every_gathered_value(dg):
     assert out.double().sum().item() == x[idx.long()].double().sum().item()
 
 
+@pytest.mark.parametrize("mode,N", [(0, 1), (1, 1), (1, 2), (1, 4), (2, 8), (2, 32), (2, 64), (2, 128), (2, 36)])
+def test_floor_probes_touch_every_entry_once(dg, mode, N):
+    """The floor probes (memory side of the kernels, no rows) are measurement aids, but what they read is checked:
+    their partial sums add up to the sum of all elements of A X, which the oracle gives.  Small integer values keep
+    every fp32 partial sum exact, so the comparison is equality."""
+    import torch
+    A = wl.rmat_csr(scale=13, avg_degree=12, seed=21)
+    rng = np.random.default_rng(22)
+    vals = rng.integers(-2, 3, size=A.nnz).astype(np.float32)
+    if mode == 0:
+        vals[:] = 1.0                                        # the bare gather does not read the values
+    X = rng.integers(-3, 4, size=(A.K, N)).astype(np.float32)
+    yref, _ = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, vals, X)
+    n_out = dg.dgsp_floor_probe_out_len(mode, N)
+    assert n_out > 0
+    out = torch.full((n_out,), float("nan"), device="cuda:0")
+    dg.dgsp_floor_probe(mode, A.K, N, torch.from_numpy(A.colidx).cuda(), torch.from_numpy(vals).cuda(),
+                        torch.from_numpy(X).cuda(), out)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+    assert out.double().sum().item() == yref.sum()
+
+
+def test_floor_probe_rejects_what_it_does_not_offer(dg):
+    import torch
+    L = dg.lib()
+    assert dg.dgsp_floor_probe_out_len(1, 3) == -1 and dg.dgsp_floor_probe_out_len(2, 6) == -1
+    assert dg.dgsp_floor_probe_out_len(7, 1) == -1
+    buf = torch.zeros(16, device="cuda:0")
+    idx = torch.zeros(16, dtype=torch.int32, device="cuda:0")
+    args = (idx.data_ptr(), buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), None)
+    assert L.dgsp_floor_probe(1, 16, 4, 3, *args) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_floor_probe(2, 16, 4, 6, *args) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_floor_probe(0, 16, 4, 2, *args) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_floor_probe(9, 16, 4, 1, *args) == dg.ERR_INVALID_ARG
+    assert L.dgsp_floor_probe(1, -1, 4, 1, *args) == dg.ERR_INVALID_ARG
+    assert L.dgsp_floor_probe(1, 16, 4, 1, idx.data_ptr(), buf.data_ptr(), buf.data_ptr(), None, None) == dg.ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("N", [1, 2, 6, 8, 64])
 def test_column_span_hint_changes_nothing_but_speed(dg, N):
     """With a matrix's features (banded: small col_span) the sequential kernels keep more loads in flight."""
@@ -343,12 +382,41 @@ def test_switched_off_optimisations_compute_the_same_product(dg, N):
     yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
     cases = [(a, dg.ABL_SCALAR_DENSE_LOADS) for a in (0, 1, 2, 3)]
     cases += [(0, dg.ABL_NO_SPARSE_STAGING), (0, dg.ABL_NO_SPARSE_STAGING | dg.ABL_SCALAR_DENSE_LOADS), (3, 0)]
+    cases += [(3, dg.ABL_ITEM_TILES), (3, dg.ABL_ITEM_TILES | dg.ABL_SCALAR_DENSE_LOADS)]
     for algo, sw in cases:
         print(f"[case] ablation N={N} algo={ALGO_NAMES[algo]} switches={sw}", flush=True)
         Y = _ablation_run(dg, A, X, algo, sw)
         assert not np.isnan(Y).any()
         ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
         assert ok, f"{ALGO_NAMES[algo]} switches={sw} N={N}: worst |err|/bound = {worst:.3e}"
+
+
+@pytest.mark.parametrize("N", [1, 2])
+@pytest.mark.parametrize("kind", ["rmat", "mostly_empty", "hub", "stencil"])
+def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
+    """At one or two dense columns per lane DGSP_NB_PR walks blocks of entries (gathers requested a block ahead);
+    the ablation switch brings back the tiles of merge-path items.  Both against the oracle, on structures that
+    stress what differs: long stretches of empty rows (several steps per block), rows spanning many blocks, and
+    short regular rows."""
+    if kind == "rmat":
+        A = wl.rmat_csr(scale=15, avg_degree=16, seed=31)
+    elif kind == "mostly_empty":
+        lens = np.zeros(300000, dtype=np.int64); lens[::1013] = 3; lens[150000] = 5000
+        A = wl.csr_from_lens(lens, 8192, seed=32, name="mostly_empty")
+    elif kind == "hub":
+        lens = np.full(5000, 1); lens[17] = 30000; lens[4000] = 9000; lens[100:900] = 0
+        A = wl.csr_from_lens(lens, 40000, seed=33, name="hub")
+    else:
+        A = wl.stencil27_csr(24, seed=34)
+    X = wl.dense_matrix(A.K, N, "uniform", seed=35 + N)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    for sw in (0, dg.ABL_ITEM_TILES):
+        print(f"[case] nb_pr pipelines {kind} N={N} switches={sw}", flush=True)
+        Y = _ablation_run(dg, A, X, dg.NB_PR, sw)
+        assert not np.isnan(Y).any()
+        ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+        assert ok, f"{kind} N={N} switches={sw}: worst |err|/bound = {worst:.3e}"
+        assert np.all(Y[A.row_lengths() == 0] == 0.0)
 
 
 def test_ablation_entry_rejects_what_it_does_not_offer(dg):
@@ -360,7 +428,8 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     L = dg.lib()
     args = (A.M, A.K, 2, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_NO_SPARSE_STAGING, None, None) == dg.ERR_UNSUPPORTED
-    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 8, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 64, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.AUTO, 0, None, None) == dg.ERR_INVALID_ARG
     torch.cuda.synchronize()
 
