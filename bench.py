@@ -552,7 +552,8 @@ def run_widths(args):
 def run_ablation(args):
     """Each optimisation of Section 2.1 against the kernel without it, on a grid of 27 R-MAT matrices
     (3 sizes x 3 densities x 3 skews; the paper's own 27 parameter sets are not published):
-    N = 1: all four kernels (which wins how often; Section 2.1.1); N = 2: vector-type dense-row loads
+    N = 1: all four kernels and the balanced kernel with a serial segment scan (which design point wins how
+    often; Section 2.1.1); N = 2: vector-type dense-row loads
     against scalar loads = two passes (Section 2.1.2); N = 128: LDS-staged sparse rows against none
     (Section 2.1.3)."""
     from paper_2106_16064_amd import binding as dg
@@ -574,6 +575,9 @@ def run_ablation(args):
                     row = {"matrix": f"rmat_s{scale}_d{deg}_{sname}", "nnz": A.nnz, "stats": A.stats()}
                     rot = Rotation(A, wl.dense_matrix(A.K, 1, "uniform", seed=0))
                     row["spmv_ms"] = variant_table(rot, k, 3)
+                    # the third alternative of Section 2.1.1: balanced, segment reduction as a serial scan
+                    row["spmv_ms"]["nb_pr_serial_scan"] = med(lambda i: rot.ablation(i, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN))
+                    row["spmv_ms"]["nb_pr_item_tiles"] = med(lambda i: rot.ablation(i, dg.NB_PR, dg.ABL_ITEM_TILES))
                     del rot
                     rot = Rotation(A, wl.dense_matrix(A.K, 2, "uniform", seed=0))
                     row["n2_ms"] = {}
@@ -596,13 +600,20 @@ def run_ablation(args):
     def geomean(v):
         return float(np.exp(np.mean(np.log(v))))
 
-    wins = {}
+    wins, design = {}, {}
+    points = ("rs_sr", "rs_pr", "nb_pr_serial_scan", "nb_pr")     # Section 2.1.1: baseline, parallel only, balance only, both
     for r in rows:
-        b = min(r["spmv_ms"], key=r["spmv_ms"].get)
+        four = {k: r["spmv_ms"][k] for k in ("rs_sr", "rs_pr", "nb_sr", "nb_pr")}
+        b = min(four, key=four.get)
         wins[b] = wins.get(b, 0) + 1
+        d = min(points, key=lambda k: r["spmv_ms"][k])
+        design[d] = design.get(d, 0) + 1
     print(json.dumps({
         "suite": "ablation", "matrices": len(rows), "file": path,
         "spmv_best_kernel_counts": wins,
+        "spmv_design_points_best_counts": design,
+        "segment_scan_dpp_vs_serial_speedup_N1": geomean([r["spmv_ms"]["nb_pr_serial_scan"] / r["spmv_ms"]["nb_pr"] for r in rows]),
+        "entry_blocks_vs_item_tiles_speedup_N1": geomean([r["spmv_ms"]["nb_pr_item_tiles"] / r["spmv_ms"]["nb_pr"] for r in rows]),
         "vector_dense_loads_speedup_N2": {a: geomean([r["n2_ms"][a + "_scalar_loads"] / r["n2_ms"][a] for r in rows])
                                           for a in ("rs_pr", "nb_pr")},
         "sparse_staging_speedup_N128": geomean([r["n128_ms"]["rs_sr_no_staging"] / r["n128_ms"]["rs_sr"] for r in rows])}))

@@ -350,12 +350,23 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                ahead, and keeps the next block's gathers in flight during the row
  *                                logic.  The comparison for that design choice.  Only DGSP_NB_PR,
  *                                else DGSP_ERR_UNSUPPORTED.
+ *   DGSP_ABL_SERIAL_SEGMENT_SCAN the balanced parallel kernel with its segment reduction done as a serial
+ *                                scan: the lanes' partial sums go to LDS and one lane adds them up in order,
+ *                                starting afresh at every row boundary.  Same balanced split, same loads: the
+ *                                workload-balanced design point WITHOUT the vectorized reduction, the third
+ *                                alternative that Section 2.1.1 measures its segment reduction against
+ *                                (beside row-split sequential and row-split parallel, which are DGSP_RS_SR and
+ *                                DGSP_RS_PR).  Only DGSP_NB_PR at widths that run one or two dense columns per
+ *                                lane (N = 1, 2, other N that 3 and 4 do not divide, or any N together with
+ *                                DGSP_ABL_SCALAR_DENSE_LOADS), not with DGSP_ABL_ITEM_TILES; else
+ *                                DGSP_ERR_UNSUPPORTED.
  * Unknown bits -> DGSP_ERR_INVALID_ARG.  algo must be one of the four kernels.
  * `features` may be NULL (host pointer otherwise; nnz and col_span are used).
  */
 #define DGSP_ABL_SCALAR_DENSE_LOADS 1
 #define DGSP_ABL_NO_SPARSE_STAGING 2
 #define DGSP_ABL_ITEM_TILES 4
+#define DGSP_ABL_SERIAL_SEGMENT_SCAN 8
 int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz,
                            const int32_t *rowptr, const int32_t *colidx, const float *vals,
                            const float *X, float *Y, int algo, int switches,

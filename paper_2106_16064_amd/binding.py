@@ -27,7 +27,7 @@ EXPORTS = (
     "dgsp_floor_probe", "dgsp_floor_probe_out_len",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
-ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING, ABL_ITEM_TILES = 1, 2, 4
+ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING, ABL_ITEM_TILES, ABL_SERIAL_SEGMENT_SCAN = 1, 2, 4, 8
 FEATURES_WORKSPACE_BYTES = 64
 PROBE_GATHER, PROBE_STREAM_GATHER_FMA, PROBE_ROW_GATHER = 0, 1, 2
 

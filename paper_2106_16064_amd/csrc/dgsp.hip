@@ -97,9 +97,18 @@ inline int direct_kernel_vector_width(const Problem& p) {
 
 // Dense columns per lane and pass of the parallel-reduction kernels: the widest of 4, 3, 2 that divides N (one
 // dwordx4 / x3 / x2 access, taken at any dword address, so alignment and leading dimensions do not matter).
-inline int pr_vector_width(const Problem& p) {
-    if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return 1;
-    return p.N % 4 == 0 ? 4 : p.N % 3 == 0 ? 3 : p.N % 2 == 0 ? 2 : 1;
+inline int pr_vector_width(int64_t N, int switches) {
+    if (switches & DGSP_ABL_SCALAR_DENSE_LOADS) return 1;
+    return N % 4 == 0 ? 4 : N % 3 == 0 ? 3 : N % 2 == 0 ? 2 : 1;
+}
+inline int pr_vector_width(const Problem& p) { return pr_vector_width(p.N, p.switches); }
+// The same for the balanced parallel kernel, which also has eight columns per lane (two dwordx4 accesses): when 8
+// divides N - one pass over A instead of two - and for N = 5, 6, 7 with the two groups of four overlapping.
+inline int nb_pr_lane_width(int64_t N, int switches) {
+    const int v = pr_vector_width(N, switches);
+    if (v == 4 && N % 8 == 0) return 8;
+    if (N >= 5 && N <= 7 && !(switches & DGSP_ABL_SCALAR_DENSE_LOADS)) return 8;
+    return v;
 }
 
 #define DGSP_LAUNCH(kernel, grid, ...)                                                        \
@@ -367,7 +376,9 @@ int launch_nb_pr_v(const Problem& p) {
             else
                 DGSP_LAUNCH((nb_pr_tiled_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
         } else if constexpr (kNbPrStreams<V>) {
-            if (p.scaled)
+            if (p.switches & DGSP_ABL_SERIAL_SEGMENT_SCAN)
+                DGSP_LAUNCH((nb_pr_kernel<V, KQ, false, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+            else if (p.scaled)
                 DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
                             Scaling{p.alpha, p.beta});
             else
@@ -378,13 +389,8 @@ int launch_nb_pr_v(const Problem& p) {
 }
 
 int launch_nb_pr(const Problem& p) {
-    // eight dense columns per lane (two dwordx4 accesses) when N allows: one pass over A instead of two
-    if (pr_vector_width(p) == 4 && p.N % 8 == 0)
-        return launch_nb_pr_v<8, 1>(p);
-    // N = 5, 6, 7: the same kernel with the lane's two groups of four columns overlapping - one pass
-    if (p.N >= 5 && p.N <= 7 && !(p.switches & DGSP_ABL_SCALAR_DENSE_LOADS))
-        return launch_nb_pr_v<8, 1>(p);
-    switch (pr_vector_width(p)) {
+    switch (nb_pr_lane_width(p.N, p.switches)) {
+        case 8: return launch_nb_pr_v<8, 1>(p);
         case 4: return launch_nb_pr_v<4, kNbPrKq>(p);
         case 3: return launch_nb_pr_v<3, kNbPrKq>(p);
         case 2: return launch_nb_pr_v<2, kNbPrKq>(p);
@@ -556,9 +562,15 @@ extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t n
                                       const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
                                       int switches, const dgsp_features_t* features, void* stream) {
     if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
-    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING | DGSP_ABL_ITEM_TILES)) return DGSP_ERR_INVALID_ARG;
+    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING | DGSP_ABL_ITEM_TILES | DGSP_ABL_SERIAL_SEGMENT_SCAN))
+        return DGSP_ERR_INVALID_ARG;
     if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
     if ((switches & DGSP_ABL_ITEM_TILES) && algo != DGSP_NB_PR) return DGSP_ERR_UNSUPPORTED;
+    if (switches & DGSP_ABL_SERIAL_SEGMENT_SCAN) {
+        // offered where the balanced parallel kernel runs its entry-block pipeline: one or two dense columns per lane
+        const bool narrow = nb_pr_lane_width(N, switches) <= 2;
+        if (algo != DGSP_NB_PR || (switches & DGSP_ABL_ITEM_TILES) || !narrow) return DGSP_ERR_UNSUPPORTED;
+    }
     if (features && nnz < 0) nnz = features->nnz;
     return run(M, K, N, nnz < 0 ? -1 : nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL,
                Hints(features), switches);

@@ -850,7 +850,11 @@ __device__ __forceinline__ void wave_merge_rows_before2(const int* __restrict__ 
     rb = uniform(lo[1]);
 }
 
-template <int V, int KQ, bool AXPBY = false>
+// SERIAL_SCAN (a comparison kernel for Section 2.1.1, not used by the library's own choices): the lanes' open-row
+// partial sums meet through a serial segmented prefix sum - they are put into LDS and one lane adds them up in
+// lane order, starting afresh at every lane that holds a row boundary - instead of the DPP network.  Everything
+// else, the balanced split included, is the same, so the difference in time is the vectorized reduction's.
+template <int V, int KQ, bool AXPBY = false, bool SERIAL_SCAN = false>
 __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N, int ldx, int ldy, const int* __restrict__ rowptr,
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
@@ -860,6 +864,7 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     constexpr int W = kWave * E;
     __shared__ __align__(16) unsigned s_bnd[kWavesPerBlock][W + 4];   // [W]: rows that end before the step's first entry
     __shared__ __align__(16) float s_buf[kWavesPerBlock][W * V];      // products, then a step's row results
+    __shared__ __align__(16) float s_scan[SERIAL_SCAN ? kWavesPerBlock : 1][SERIAL_SCAN ? kWave * (V + 1) : 1];   // serial scan only
     const int lane = lane_id();
     const int wib = wave_in_block();
     unsigned* bnd = s_bnd[wib];
@@ -1070,8 +1075,33 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
 
         // ---- the open row across lanes: segments start at lanes that hold a boundary
         const bool flagged = head_row != kNoRow;
-        const int head_lane = (int)wave_max_scan(flagged ? (unsigned)lane : 0u);
-        segmented_scan<V>(s, lane - head_lane, lane);      // s: sum of the open row up to and including my lane
+        if constexpr (SERIAL_SCAN) {
+            float* sc_val = s_scan[wib];                   // 64 x V partial sums, then 64 flags
+            float* sc_flag = sc_val + kWave * V;
+#pragma unroll
+            for (int i = 0; i < V; ++i) sc_val[lane * V + i] = s[i];
+            sc_flag[lane] = flagged ? 1.0f : 0.0f;
+            wave_lds_sync();
+            if (lane == 0) {
+                float run[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i) run[i] = 0.0f;
+                for (int l = 0; l < kWave; ++l) {          // one lane, lane order: a boundary starts a new sum
+                    const bool start = sc_flag[l] != 0.0f;
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        run[i] = (start ? 0.0f : run[i]) + sc_val[l * V + i];
+                        sc_val[l * V + i] = run[i];
+                    }
+                }
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int i = 0; i < V; ++i) s[i] = sc_val[lane * V + i];
+        } else {
+            const int head_lane = (int)wave_max_scan(flagged ? (unsigned)lane : 0u);
+            segmented_scan<V>(s, lane - head_lane, lane);  // s: sum of the open row up to and including my lane
+        }
         {
             float closing[V];
 #pragma unroll

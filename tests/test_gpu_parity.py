@@ -383,6 +383,7 @@ def test_switched_off_optimisations_compute_the_same_product(dg, N):
     cases = [(a, dg.ABL_SCALAR_DENSE_LOADS) for a in (0, 1, 2, 3)]
     cases += [(0, dg.ABL_NO_SPARSE_STAGING), (0, dg.ABL_NO_SPARSE_STAGING | dg.ABL_SCALAR_DENSE_LOADS), (3, 0)]
     cases += [(3, dg.ABL_ITEM_TILES), (3, dg.ABL_ITEM_TILES | dg.ABL_SCALAR_DENSE_LOADS)]
+    cases += [(3, dg.ABL_SERIAL_SEGMENT_SCAN | dg.ABL_SCALAR_DENSE_LOADS)] + ([(3, dg.ABL_SERIAL_SEGMENT_SCAN)] if N in (1, 2, 130) else [])
     for algo, sw in cases:
         print(f"[case] ablation N={N} algo={ALGO_NAMES[algo]} switches={sw}", flush=True)
         Y = _ablation_run(dg, A, X, algo, sw)
@@ -397,7 +398,8 @@ def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
     """At one or two dense columns per lane DGSP_NB_PR walks blocks of entries (gathers requested a block ahead);
     the ablation switch brings back the tiles of merge-path items.  Both against the oracle, on structures that
     stress what differs: long stretches of empty rows (several steps per block), rows spanning many blocks, and
-    short regular rows."""
+    short regular rows.  The third variant replaces the DPP segment reduction by a serial scan (the comparison
+    kernel of Section 2.1.1)."""
     if kind == "rmat":
         A = wl.rmat_csr(scale=15, avg_degree=16, seed=31)
     elif kind == "mostly_empty":
@@ -410,7 +412,7 @@ def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
         A = wl.stencil27_csr(24, seed=34)
     X = wl.dense_matrix(A.K, N, "uniform", seed=35 + N)
     yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
-    for sw in (0, dg.ABL_ITEM_TILES):
+    for sw in (0, dg.ABL_ITEM_TILES, dg.ABL_SERIAL_SEGMENT_SCAN):
         print(f"[case] nb_pr pipelines {kind} N={N} switches={sw}", flush=True)
         Y = _ablation_run(dg, A, X, dg.NB_PR, sw)
         assert not np.isnan(Y).any()
@@ -430,6 +432,10 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_NO_SPARSE_STAGING, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 64, None, None) == dg.ERR_INVALID_ARG
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_PR, dg.ABL_SERIAL_SEGMENT_SCAN, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN | dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
+    args4 = (A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
+    assert L.dgsp_spmm_csr_ablation(*args4, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.AUTO, 0, None, None) == dg.ERR_INVALID_ARG
     torch.cuda.synchronize()
 
