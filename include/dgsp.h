@@ -272,6 +272,28 @@ int dgsp_autotune(int64_t M, int64_t K, int64_t N, int64_t nnz,
                   int reps, float *ms, int *best, void *stream);
 
 /*
+ * The same multiplication for matrices whose row pointers are 64-bit (the paper leaves the index type open;
+ * this is for more than 2^31 - 4096 stored entries, which the other entry points reject).  Column indices stay
+ * int32 (K within the int32 range), as do M and N.
+ *   rowptr     device, int64[M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz
+ *   nnz        the number of stored entries (>= 0; it sizes the workspace, so the caller has to know it)
+ *   workspace  device, dgsp_spmm_csr_i64_workspace_bytes(M, nnz) bytes (4 (M + 1) and a few hundred more),
+ *              16-byte aligned, caller-owned, overwritten
+ * How: the rows are cut into slabs that hold about 2^30 entries each; per slab a small launch writes 32-bit row
+ * pointers relative to the slab's first entry into the workspace, and the chosen kernel runs on the slab (its
+ * rows of Y are disjoint from every other slab's).  No row may hold 2^30 entries or more, and at most 15 slabs
+ * are taken: else DGSP_ERR_UNSUPPORTED.  The slab cuts are found on the device and decide launch sizes, so the
+ * call WAITS once for `stream` (a 200-byte copy) before it enqueues the slabs; it returns after enqueueing them.
+ * algo: one of the four kernels, or DGSP_AUTO = the balanced kernel for the width, as in dgsp_spmm_csr.
+ * Other arguments, result and errors as dgsp_spmm_csr_nnz; a wrong nnz or rowptr[0] != 0 -> DGSP_ERR_INVALID_ARG.
+ */
+int dgsp_spmm_csr_i64(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                      const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                      const float *X, float *Y, int algo,
+                      void *workspace, int64_t workspace_bytes, void *stream);
+int64_t dgsp_spmm_csr_i64_workspace_bytes(int64_t M, int64_t nnz);
+
+/*
  * Measurement aid: the same multiplication, one step at a time.  The two
  * nnz-balanced kernels are two launches per call - a small "prepare" launch
  * (zeroes the rows that are later combined with atomic adds) and the main

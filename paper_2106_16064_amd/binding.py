@@ -24,7 +24,7 @@ EXPORTS = (
     "dgsp_spmm_csr_phase", "dgsp_gather_probe", "dgsp_gather_probe_out_len", "dgsp_features_from_csr_host",
     "dgsp_spmm_csr_ablation", "dgsp_features_from_csr_device", "dgsp_autotune",
     "dgsp_spmm_csr_ld", "dgsp_spmm_csr_axpby", "dgsp_features_from_csr_device_noalloc",
-    "dgsp_floor_probe", "dgsp_floor_probe_out_len",
+    "dgsp_floor_probe", "dgsp_floor_probe_out_len", "dgsp_spmm_csr_i64", "dgsp_spmm_csr_i64_workspace_bytes",
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING, ABL_ITEM_TILES, ABL_SERIAL_SEGMENT_SCAN = 1, 2, 4, 8
@@ -106,6 +106,10 @@ def lib():
         L.dgsp_gather_probe.argtypes = [vp, vp, vp, i64, vp]
         L.dgsp_gather_probe_out_len.restype = i64
         L.dgsp_gather_probe_out_len.argtypes = []
+        L.dgsp_spmm_csr_i64.restype = ci
+        L.dgsp_spmm_csr_i64.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp, i64, vp]
+        L.dgsp_spmm_csr_i64_workspace_bytes.restype = i64
+        L.dgsp_spmm_csr_i64_workspace_bytes.argtypes = [i64, i64]
         L.dgsp_floor_probe.restype = ci
         L.dgsp_floor_probe.argtypes = [ci, i64, i64, i64, vp, vp, vp, vp, vp]
         L.dgsp_floor_probe_out_len.restype = i64
@@ -164,6 +168,26 @@ def dgsp_spmm_csr_nnz(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, stream=Non
     rc = lib().dgsp_spmm_csr_nnz(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y),
                                  int(algo), _stream(stream))
     _check(rc, "dgsp_spmm_csr_nnz")
+
+
+def dgsp_spmm_csr_i64(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo=AUTO, workspace=None, stream=None):
+    """``Y = A X`` with int64 row pointers (more than 2^31 stored entries).  ``workspace``: a uint8 GPU tensor of
+    ``dgsp_spmm_csr_i64_workspace_bytes(M, nnz)`` bytes (made here if not given).  Waits once for the stream."""
+    import torch
+    if not rowptr.is_cuda or rowptr.dtype != torch.int64 or not rowptr.is_contiguous() or rowptr.numel() != M + 1:
+        raise DgspError("rowptr must be a contiguous int64 GPU tensor of M+1 entries")
+    for name, t, dt in (("colidx", colidx, torch.int32), ("vals", vals, torch.float32), ("X", X, torch.float32),
+                        ("Y", Y, torch.float32)):
+        if not t.is_cuda or t.dtype != dt or not t.is_contiguous():
+            raise DgspError(f"{name} must be a contiguous {dt} tensor on the GPU")
+    if colidx.numel() < nnz or vals.numel() < nnz or X.numel() != K * N or Y.numel() != M * N:
+        raise DgspError("colidx and vals need nnz entries, X K*N and Y M*N elements")
+    need = int(lib().dgsp_spmm_csr_i64_workspace_bytes(M, int(nnz)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=rowptr.device)
+    rc = lib().dgsp_spmm_csr_i64(M, K, N, int(nnz), _ptr(rowptr), _ptr(colidx), _ptr(vals), _ptr(X), _ptr(Y), int(algo),
+                                 _ptr(workspace), int(workspace.numel()), _stream(stream))
+    _check(rc, "dgsp_spmm_csr_i64")
 
 
 def dgsp_spmm_csr_phase(M, K, N, nnz, rowptr, colidx, vals, X, Y, algo, phase, features=None, stream=None):

@@ -587,6 +587,60 @@ extern "C" int dgsp_spmm_csr_auto(int64_t M, int64_t K, int64_t N, const dgsp_fe
     return run(M, K, N, features->nnz, rowptr, colidx, vals, X, Y, algo, stream, DGSP_PHASE_ALL, Hints(features));
 }
 
+// ---------------------------------------------------------------- 64-bit row pointers
+namespace {
+constexpr int64_t kSlabEntries = 1ll << 30;        // a slab holds this many entries plus at most one row more
+inline int64_t slab_count(int64_t nnz) { return nnz <= 0 ? 1 : (nnz + kSlabEntries - 1) / kSlabEntries; }
+inline int64_t round_up16(int64_t v) { return (v + 15) / 16 * 16; }
+}  // namespace
+
+extern "C" int64_t dgsp_spmm_csr_i64_workspace_bytes(int64_t M, int64_t nnz) {
+    if (M < 0 || nnz < 0) return -1;
+    return round_up16(4 * (M + 1)) + 16 * (slab_count(nnz) + 1);
+}
+
+extern "C" int dgsp_spmm_csr_i64(int64_t M, int64_t K, int64_t N, int64_t nnz, const int64_t* rowptr, const int32_t* colidx,
+                                 const float* vals, const float* X, float* Y, int algo, void* workspace,
+                                 int64_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || N < 0 || nnz < 0) return DGSP_ERR_INVALID_ARG;
+    if (algo < DGSP_AUTO || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return DGSP_OK;
+    const int64_t lim = (int64_t)INT32_MAX - 4096;
+    if (M > lim || K > lim || N > lim) return DGSP_ERR_INVALID_ARG;
+    if (!rowptr || !Y || (nnz > 0 && (!colidx || !vals || !X || K == 0))) return DGSP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 16) || workspace_bytes < dgsp_spmm_csr_i64_workspace_bytes(M, nnz))
+        return DGSP_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int nslabs = (int)slab_count(nnz);
+    int* rowptr32 = static_cast<int*>(workspace);
+    long long* cuts = reinterpret_cast<long long*>(static_cast<char*>(workspace) + round_up16(4 * (M + 1)));
+    hipLaunchKernelGGL(i64_slab_bounds_kernel, dim3((unsigned)((nslabs + 1 + kWave - 1) / kWave)), dim3(kWave), 0, st,
+                       (long long)M, reinterpret_cast<const long long*>(rowptr), nslabs, (long long)kSlabEntries, cuts);
+    if (hipGetLastError() != hipSuccess) return DGSP_ERR_LAUNCH;
+    // the cuts decide launch sizes, so the host has to see them: the one wait of this entry point
+    long long h[2 * 16];
+    if (nslabs + 1 > 16) return DGSP_ERR_UNSUPPORTED;                   // 15 * 2^30 entries and more
+    if (hipMemcpyAsync(h, cuts, sizeof(long long) * 2 * (size_t)(nslabs + 1), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return DGSP_ERR_LAUNCH;
+    if (hipStreamSynchronize(st) != hipSuccess) return DGSP_ERR_LAUNCH;
+    if (h[1] != 0 || h[2 * nslabs + 1] != nnz) return DGSP_ERR_INVALID_ARG;      // rowptr[0] != 0 or rowptr[M] != nnz
+    for (int k = 0; k < nslabs; ++k)
+        if (h[2 * k + 3] - h[2 * k + 1] > lim || h[2 * k + 3] < h[2 * k + 1] || h[2 * k + 2] < h[2 * k]) return DGSP_ERR_UNSUPPORTED;
+    for (int k = 0; k < nslabs; ++k) {
+        const int64_t first = h[2 * k], rows = h[2 * k + 2] - first;
+        const int64_t base = h[2 * k + 1], entries = h[2 * k + 3] - base;
+        if (rows == 0) continue;
+        const long long cap = (long long)device_info().cus * kBlocksPerCu * 4;
+        hipLaunchKernelGGL(i64_slab_rowptr_kernel, dim3(clamp_blocks((rows + 1 + kBlock - 1) / kBlock, cap)), dim3(kBlock), 0, st,
+                           (long long)rows, reinterpret_cast<const long long*>(rowptr) + first, (long long)base, rowptr32);
+        if (hipGetLastError() != hipSuccess) return DGSP_ERR_LAUNCH;
+        const int rc = run(rows, K, N, entries, rowptr32, colidx ? colidx + base : nullptr, vals ? vals + base : nullptr, X,
+                           Y + (size_t)first * (size_t)N, algo, stream);
+        if (rc != DGSP_OK) return rc;
+    }
+    return DGSP_OK;
+}
+
 // Section 2.2: N picks the reduction, row-length statistics pick the partition.
 extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     if (!f || N < 1) return DGSP_AUTO;

@@ -1600,6 +1600,38 @@ __global__ __launch_bounds__(kBlock) void features_kernel(int M, const int* __re
 }
 
 // ===========================================================================
+// 64-bit row pointers: slabs of rows whose entry positions fit 32 bits
+// ===========================================================================
+// The kernels address entries with 32-bit positions.  A matrix with more than 2^31 stored entries is cut into
+// slabs of consecutive rows: slab k starts at the first row whose pointer reaches k * slab_entries.  One thread
+// per cut: out[2k] = the row, out[2k+1] = its pointer (the slab's base); cut nslabs is (M, rowptr[M]).
+__global__ void i64_slab_bounds_kernel(long long M, const long long* __restrict__ rowptr, int nslabs, long long slab_entries,
+                                       long long* __restrict__ out) {
+    const int k = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (k > nslabs) return;
+    long long r = M;
+    if (k < nslabs) {
+        const long long target = (long long)k * slab_entries;
+        long long lo = 0, hi = M;                       // first r in [0, M] with rowptr[r] >= target
+        while (lo < hi) {
+            const long long mid = lo + (hi - lo) / 2;
+            if (rowptr[mid] < target) lo = mid + 1; else hi = mid;
+        }
+        r = lo;
+    }
+    out[2 * k] = r;
+    out[2 * k + 1] = rowptr[r];
+}
+
+// The 32-bit row pointers of one slab: out[i] = rowptr[first + i] - base for i in [0, rows].
+__global__ __launch_bounds__(kBlock) void i64_slab_rowptr_kernel(long long rows, const long long* __restrict__ rowptr_first,
+                                                                  long long base, int* __restrict__ out) {
+    const long long nthreads = (long long)gridDim.x * kBlock;
+    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i <= rows; i += nthreads)
+        out[i] = (int)(rowptr_first[i] - base);
+}
+
+// ===========================================================================
 // measurement aids: pure gather, the memory side of the parallel and of the sequential kernels, plain streaming copy
 // ===========================================================================
 

@@ -169,6 +169,89 @@ def test_more_than_two_to_the_thirty_entries(dg):
             assert ok, f"{NAMES[algo]} N={N}: worst |err|/bound {worst:.3e}"
 
 
+# ------------------------------------------------------------------ 64-bit row pointers, more than 2^31 stored entries
+def test_sixty_four_bit_row_pointers_small(dg):
+    """dgsp_spmm_csr_i64 on matrices the other entry points take as well: the same products, every kernel."""
+    import torch
+    for A, N in ((wl.rmat_csr(scale=14, avg_degree=16, seed=51), 1), (wl.poisson_csr(3000, 2000, 9.0, seed=52), 4),
+                 (wl.csr_from_lens(np.zeros(500, dtype=np.int64), 40, seed=53, name="no_entries"), 3)):
+        X = wl.dense_matrix(A.K, N, "uniform", seed=54)
+        yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+        rp = torch.from_numpy(A.rowptr.astype(np.int64)).cuda()
+        ci, va = torch.from_numpy(A.colidx).cuda(), torch.from_numpy(A.vals).cuda()
+        dX = torch.from_numpy(X).cuda()
+        for algo in (-1, 0, 1, 2, 3):
+            print(f"[case] i64 {A.name} N={N} algo={NAMES[algo]}", flush=True)
+            dY = torch.full((A.M, N), float("nan"), device="cuda:0")
+            dg.dgsp_spmm_csr_i64(A.M, A.K, N, A.nnz, rp, ci, va, dX, dY, algo)
+            torch.cuda.synchronize()
+            ok, worst = oracle.within_bound(dY.cpu().numpy(), yref, bnd, TOL)
+            assert ok, f"{NAMES[algo]} on {A.name}: worst |err|/bound {worst:.3e}"
+    # a wrong entry count, a short workspace and a 32-bit-style misuse are refused
+    L = dg.lib()
+    A = wl.poisson_csr(300, 200, 5.0, seed=55)
+    rp = torch.from_numpy(A.rowptr.astype(np.int64)).cuda()
+    ci, va = torch.from_numpy(A.colidx).cuda(), torch.from_numpy(A.vals).cuda()
+    dX = torch.zeros((A.K, 1), device="cuda:0"); dY = torch.zeros((A.M, 1), device="cuda:0")
+    big = torch.empty(1 << 16, dtype=torch.uint8, device="cuda:0")
+    args = (rp.data_ptr(), ci.data_ptr(), va.data_ptr(), dX.data_ptr(), dY.data_ptr(), 3)
+    assert L.dgsp_spmm_csr_i64(A.M, A.K, 1, A.nnz + 1, *args, big.data_ptr(), big.numel(), None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_i64(A.M, A.K, 1, A.nnz, *args, big.data_ptr(), 64, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_i64(A.M, A.K, 1, A.nnz, *args, None, 1 << 16, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_i64(A.M, A.K, 1, -1, *args, big.data_ptr(), big.numel(), None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_i64(A.M, A.K, 1, A.nnz, *args, big.data_ptr(), big.numel(), None) == dg.OK
+    torch.cuda.synchronize()
+
+
+def test_more_than_two_to_the_thirty_one_entries(dg):
+    """2.68e9 stored entries behind 64-bit row pointers: entry positions pass 2^31, so the matrix is only reachable
+    through dgsp_spmm_csr_i64, which cuts it into three slabs.  Built on the device from the closed form of
+    big_entries(); the oracle recomputes sampled rows on the host - among them the rows on both sides of every slab
+    cut (entry positions 2^30 and 2^31), around position 2^31 + 2^30 bytes apart, and both ends."""
+    import torch
+    dev = torch.device("cuda:0")
+    M = 1 << 21
+    rows = torch.arange(M, dtype=torch.int64, device=dev)
+    lens = 1024 + (rows % 512)
+    rowptr = torch.zeros(M + 1, dtype=torch.int64, device=dev)
+    rowptr[1:] = torch.cumsum(lens, 0)
+    nnz = int(rowptr[-1])
+    assert nnz > (1 << 31)
+    colidx = torch.empty(nnz, dtype=torch.int32, device=dev)
+    vals = torch.empty(nnz, dtype=torch.float32, device=dev)
+    step = 1 << 26
+    for lo in range(0, nnz, step):
+        p = torch.arange(lo, min(lo + step, nnz), dtype=torch.int64, device=dev)
+        i = torch.searchsorted(rowptr, p, right=True) - 1
+        j = p - rowptr[i]
+        colidx[lo:lo + p.numel()] = ((977 * i + 811 * j) % BIG_K).to(torch.int32)
+        vals[lo:lo + p.numel()] = ((40503 * p) % 65536).to(torch.float32) / 65536.0 - 0.5
+    del p, i, j, rows, lens
+    rp = rowptr.cpu().numpy()
+    cuts = [int(np.searchsorted(rp, k << 30)) for k in (1, 2)]
+    sample = np.unique(np.concatenate(
+        [np.random.default_rng(6).integers(0, M, size=1200), np.arange(0, 66), np.arange(M - 66, M)]
+        + [np.arange(c - 70, c + 70) for c in cuts]))
+    slens, scol, sval = big_entries(sample)
+    assert np.array_equal(slens, np.diff(rp)[sample])
+    srowptr = np.zeros(sample.size + 1, dtype=np.int32)
+    srowptr[1:] = np.cumsum(slens)
+    workspace = torch.empty(dg.lib().dgsp_spmm_csr_i64_workspace_bytes(M, nnz), dtype=torch.uint8, device=dev)
+    for N, algos in ((1, (-1, 3, 2, 1, 0)), (4, (2, 0))):
+        X = wl.dense_matrix(BIG_K, N, "uniform", seed=60 + N)
+        yref, bnd = oracle.spmm_ref(sample.size, BIG_K, N, srowptr, scol, sval, X)
+        dX = torch.from_numpy(X).cuda()
+        for algo in algos:
+            print(f"[case] 2.68e9 entries (int64 row pointers) N={N} algo={NAMES[algo]}", flush=True)
+            dY = torch.full((M, N), float("nan"), device=dev)
+            dg.dgsp_spmm_csr_i64(M, BIG_K, N, nnz, rowptr, colidx, vals, dX, dY, algo, workspace)
+            torch.cuda.synchronize()
+            assert not bool(torch.isnan(dY).any())
+            Y = dY[torch.from_numpy(sample).cuda()].cpu().numpy()
+            ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+            assert ok, f"{NAMES[algo]} N={N}: worst |err|/bound {worst:.3e}"
+
+
 # ------------------------------------------------------------------ dense operands beyond 4 GB
 def test_dense_operands_beyond_four_gigabytes(dg, rmat20):
     """X and Y as column slices of 2^20 x 1100 buffers (4.6 GB each): byte offsets into them pass 2^32, so the
