@@ -22,6 +22,7 @@ and writes its per-cell records under RESULTS_DIR):
     --suite tiny      the launch-bound 4096^2 configuration, eager launches against HIP graph replay
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
     --suite widths    the adaptive call at 34 dense widths from 1 to 128 on three matrices
+    --suite holdout   the shipped selection rules scored on matrices they were not fitted on
 """
 from __future__ import annotations
 
@@ -533,14 +534,34 @@ def run_widths(args):
             ("Poisson(16) rows, 2^18 rows", lambda: wl.sweep_csr(1 << 18, 16, "poisson", 0)),
             ("27-point stencil 64^3", lambda: wl.stencil27_csr(64, seed=0))]
     cells = 0
+    pad = args.ld_multiple
     with open(path, "w") as fh:
         for label, gen in mats:
             A = gen()
             for n in widths:
                 rot = Rotation(A, wl.dense_matrix(A.K, n, "uniform", seed=0))
-                us = median(time_events(None, lambda i: rot.step(i, dg.AUTO), max(5, min(args.steps, 30)), 3)) * 1e3
+                if pad:
+                    # rows of X and Y padded to a multiple of `pad` floats and passed as views: what the library
+                    # recommends to callers with odd widths (rows then start on line boundaries)
+                    import torch
+                    ld = -(-n // pad) * pad
+                    Xp = [torch.zeros((A.K, ld), dtype=torch.float32, device="cuda:0") for _ in range(rot.copies)]
+                    Yp = [torch.empty((A.M, ld), dtype=torch.float32, device="cuda:0") for _ in range(rot.copies)]
+                    for j in range(rot.copies):
+                        Xp[j][:, :n] = rot.X[j]
+
+                    def call(i):
+                        j = i % rot.copies
+                        m = rot.mats[j]
+                        dg.dgsp_spmm_csr_ld(m.M, m.K, n, m.nnz, m.rowptr, m.colidx, m.vals, Xp[j][:, :n], Yp[j][:, :n],
+                                            dg.AUTO, m.features)
+                else:
+                    def call(i):
+                        rot.step(i, dg.AUTO)
+                us = median(time_events(None, call, max(5, min(args.steps, 30)), 3)) * 1e3
                 sel = dg.dgsp_algo_name(dg.dgsp_select_algo(rot.mats[0].features, n))
-                fh.write(json.dumps({"matrix": label, "N": n, "nnz": A.nnz, "us": us, "selected": sel}) + "\n")
+                fh.write(json.dumps({"matrix": label, "N": n, "nnz": A.nnz, "us": us, "selected": sel,
+                                     "ld": (-(-n // pad) * pad) if pad else n}) + "\n")
                 fh.flush()
                 cells += 1
                 del rot
@@ -560,7 +581,7 @@ def run_ablation(args):
     from paper_2106_16064_amd import workloads as wl
     os.makedirs(RESULTS_DIR, exist_ok=True)
     path = os.path.join(RESULTS_DIR, args.out or "bench_ablation.jsonl")
-    skews = {"powerlaw": (0.57, 0.19, 0.19, 0.05), "mild": (0.45, 0.15, 0.15, 0.25), "uniform": (0.25, 0.25, 0.25, 0.25)}
+    skews = RMAT_GRID_SKEWS
     k = max(5, min(args.steps, 20))
 
     def med(fn):
@@ -617,6 +638,51 @@ def run_ablation(args):
         "vector_dense_loads_speedup_N2": {a: geomean([r["n2_ms"][a + "_scalar_loads"] / r["n2_ms"][a] for r in rows])
                                           for a in ("rs_pr", "nb_pr")},
         "sparse_staging_speedup_N128": geomean([r["n128_ms"]["rs_sr_no_staging"] / r["n128_ms"]["rs_sr"] for r in rows])}))
+    return 0
+
+
+RMAT_GRID_SKEWS = {"powerlaw": (0.57, 0.19, 0.19, 0.05), "mild": (0.45, 0.15, 0.15, 0.25), "uniform": (0.25, 0.25, 0.25, 0.25)}
+
+
+def run_holdout(args):
+    """Scores the shipped selection rules on inputs they were not fitted on: the 27-matrix R-MAT grid of the
+    ablation suite (3 sizes x 3 densities x 3 skews) and seven further row-length laws at 2^18 rows
+    (workloads.HOLDOUT_LAWS), each at N in {1, 4, 8, 32, 128}; all four kernels timed per cell, loss of the rules'
+    choice against the fastest.  Reports mean, worst and the cells above 10 %."""
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_holdout.jsonl")
+    gens = [(f"rmat_s{scale}_d{deg}_{sname}", lambda scale=scale, deg=deg, abcd=abcd: wl.rmat_csr(scale, deg, abcd, seed=0, values="uniform01"))
+            for scale in (16, 18, 20) for deg in (4, 16, 32) for sname, abcd in RMAT_GRID_SKEWS.items()]
+    gens += [(f"law_{law}", lambda law=law: wl.holdout_law_csr(law, 1 << 18, seed=0)) for law in wl.HOLDOUT_LAWS]
+    if args.workload:
+        gens = [g for g in gens if g[0].startswith(args.workload)]
+    k = max(5, min(args.steps, 10))
+    cells = []
+    with open(path, "w") as fh:
+        for name, gen in gens:
+            A = gen()
+            for n in (1, 4, 8, 32, 128):
+                rot = Rotation(A, wl.dense_matrix(A.K, n, "uniform", seed=0), copies=2 if A.nnz * n > 3e8 else None)
+                table = variant_table(rot, k, 2)
+                f = rot.mats[0].features
+                sel = dg.dgsp_algo_name(dg.dgsp_select_algo(f, n))
+                best = min(table, key=table.get)
+                rec = {"matrix": name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row, "max_row": f.max_row, "nnz": A.nnz,
+                       "K": A.K, "col_span": f.col_span, "ms": table, "selected": sel, "best": best,
+                       "loss": table[sel] / table[best] - 1.0}
+                cells.append(rec)
+                fh.write(json.dumps(rec) + "\n")
+                fh.flush()
+                del rot
+            print(f"[holdout] {name} done", file=sys.stderr, flush=True)
+    losses = [c["loss"] for c in cells]
+    over = [c for c in cells if c["loss"] > 0.10]
+    print(json.dumps({"suite": "holdout", "cells": len(cells), "file": path, "mean_loss": sum(losses) / len(losses),
+                      "worst_loss": max(losses), "cells_over_10pct": len(over),
+                      "over_10pct": [{"matrix": c["matrix"], "N": c["N"], "selected": c["selected"], "best": c["best"],
+                                      "loss": round(c["loss"], 3)} for c in over]}))
     return 0
 
 
@@ -744,7 +810,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths", "holdout"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -752,6 +818,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="kernel suite: also run five 1 GiB dgsp_copy_f32 launches (byte-counter calibration)")
     ap.add_argument("--no-cells", action="store_true", help="default suite: only the headline workload, no further cells")
+    ap.add_argument("--ld-multiple", type=int, default=0,
+                    help="widths suite: pad the rows of X and Y to a multiple of this many floats and pass views")
     ap.add_argument("--sweep-m", type=int, default=1 << 18)
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
@@ -767,7 +835,8 @@ def main():
     from paper_2106_16064_amd import binding as dg
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
-            "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel, "widths": run_widths}[args.suite](args)
+            "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel, "widths": run_widths,
+            "holdout": run_holdout}[args.suite](args)
 
 
 if __name__ == "__main__":

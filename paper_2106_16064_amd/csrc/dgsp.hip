@@ -315,13 +315,9 @@ int launch_prepare(const Problem& p, unsigned parts, unsigned quantum_log2, int 
 //     that nothing overlaps yet) and fewer waves leave more of the L1 to each - but two as soon as
 //     that leaves a wave 6 tiles (measured on matrices of 1 M to 57 M entries).
 constexpr long long kNbPrTilesPerWave = 12;
-#ifndef DGSP_X_KQ
-#define DGSP_X_KQ 2
-#endif
-#ifndef DGSP_X_PRCU
-#define DGSP_X_PRCU 0
-#endif
-constexpr int kNbPrKq = DGSP_X_KQ;          // quads of entries per lane and tile in the balanced parallel kernel (V <= 4)
+// quads of entries per lane and tile / block in the balanced parallel kernel for up to four columns per lane
+// (four quads, 1024 items: 4-8 % faster on the stencil with item tiles, 2-12 % slower with entry blocks and on R-MAT)
+constexpr int kNbPrKq = 2;
 
 inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per_cu, bool parallel,
                                 long long col_blocks = 1) {
@@ -336,7 +332,6 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
     if (parallel) {
         per_cu = tiles / (waves * kNbPrTilesPerWave);
         if (per_cu < 2) per_cu = tiles >= waves * kNbPrTilesPerWave ? 2 : 1;
-        if (DGSP_X_PRCU > 0) per_cu = DGSP_X_PRCU;
     } else {
         // the column blocks of a wide X (grid.y) are resident side by side: count them in
         const long long want = (tiles * col_blocks + waves - 1) / waves;
@@ -715,10 +710,9 @@ extern "C" int dgsp_gather_probe(float* out, const float* x, const int32_t* idx,
 
 // ---------------------------------------------------------------- floor probes (measurement aids)
 namespace {
-#ifndef DGSP_X_PROBE_BLOCKS
-#define DGSP_X_PROBE_BLOCKS 1024
-#endif
-constexpr int kStreamProbeBlocks = DGSP_X_PROBE_BLOCKS;        // four workgroups per CU: what the lean pipeline ran best with
+// four workgroups per CU: what the lean pipeline ran best with (512 / 1024 / 1280 / 2048 workgroups on the R-MAT
+// SpMV: 79 / 82 / 90 / 86 us; on the stencil: 118 / 110 / 152 / 114 us)
+constexpr int kStreamProbeBlocks = 1024;
 
 struct RowProbeShape { int logG; unsigned col_blocks; unsigned blocks; };
 RowProbeShape row_probe_shape(int64_t N) {

@@ -1666,10 +1666,7 @@ template <int V>
 __global__ __launch_bounds__(kBlock) void stream_gather_fma_probe_kernel(float* __restrict__ out, const float* __restrict__ X,
                                                                          long long K, int ldx, const int* __restrict__ colidx,
                                                                          const float* __restrict__ vals, long long nnz) {
-#ifndef DGSP_X_PROBE_E
-#define DGSP_X_PROBE_E 8
-#endif
-    constexpr int E = DGSP_X_PROBE_E;
+    constexpr int E = 8;
     constexpr long long W = kWave * E;
     const int lane = lane_id();
     const long long nwaves = (long long)gridDim.x * kWavesPerBlock;

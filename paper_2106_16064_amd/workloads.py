@@ -268,6 +268,40 @@ def sweep_matrices(M=1 << 18):
                 yield sweep_csr(M, mean, dist, seed)
 
 
+HOLDOUT_LAWS = ("poisson9", "pareto", "alike27", "bursts", "one_giant", "tile_widths", "half_empty")
+
+
+def holdout_law_csr(law: str, M=1 << 18, seed=0) -> CsrMatrix:
+    """Matrices for scoring the selection rules on row-length laws they were NOT fitted on (the sweep's four laws
+    are what the thresholds come from): Poisson(9); a heavy Pareto tail; all rows 27 long; long empty stretches with
+    short bursts; Poisson(3) with one 20 000-entry row; lengths around the wave and tile widths (0 ... 257); Poisson(5)
+    with the second half of the rows empty.  K = M, distinct uniform columns, values U(-1,1).
+    Draw order: lengths, columns, values."""
+    rng = np.random.default_rng([seed, 0x401d, HOLDOUT_LAWS.index(law)])
+    if law == "poisson9":
+        lens = rng.poisson(9.0, size=M)
+    elif law == "pareto":
+        lens = np.floor(rng.pareto(1.2, size=M) * 6.0).astype(np.int64)
+    elif law == "alike27":
+        lens = np.full(M, 27)
+    elif law == "bursts":
+        lens = np.zeros(M, dtype=np.int64)
+        hot = rng.random(M) < 0.02
+        lens[hot] = rng.integers(1, 20, size=int(hot.sum()))
+    elif law == "one_giant":
+        lens = rng.poisson(3.0, size=M)
+        lens[int(rng.integers(0, M))] = 20000
+    elif law == "tile_widths":
+        lens = rng.choice([0, 1, 63, 64, 65, 127, 128, 129, 255, 256, 257], size=M)
+    elif law == "half_empty":
+        lens = rng.poisson(5.0, size=M)
+        lens[M // 2:] = 0
+    else:
+        raise ValueError(law)
+    return _from_lens(np.minimum(lens, M), M, rng, f"holdout_{law}_M{M}_s{seed}",
+                      lambda n: rng.uniform(-1.0, 1.0, size=n), dict(kind="holdout", law=law, seed=seed))
+
+
 def csr_from_lens(lens, K, seed=0, name="custom") -> CsrMatrix:
     """CSR with the given row lengths, distinct uniform columns, values U(-1,1)."""
     rng = np.random.default_rng(seed)
