@@ -433,7 +433,7 @@ def run_sweep(args):
                 best = min(table, key=table.get)
                 loss = table[sel] / table[best] - 1.0
                 losses.append(loss)
-                fh.write(json.dumps({"matrix": A.name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row,
+                fh.write(json.dumps({"matrix": A.name, "N": n, "M": A.M, "avg_row": f.avg_row, "cv_row": f.cv_row,
                                      "max_row": f.max_row, "nnz": A.nnz, "K": A.K, "col_span": f.col_span, "ms": table, "selected": sel,
                                      "best": best, "loss": loss}) + "\n")
                 fh.flush()
@@ -511,7 +511,7 @@ def run_size(args):
                 f = rot.mats[0].features
                 sel = dg.dgsp_algo_name(dg.dgsp_select_algo(f, n))
                 best = min(table, key=table.get)
-                fh.write(json.dumps({"matrix": name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row,
+                fh.write(json.dumps({"matrix": name, "N": n, "M": A.M, "avg_row": f.avg_row, "cv_row": f.cv_row,
                                      "max_row": f.max_row, "nnz": A.nnz, "K": A.K, "col_span": f.col_span, "ms": table, "selected": sel,
                                      "best": best, "loss": table[sel] / table[best] - 1.0}) + "\n")
                 fh.flush()
@@ -669,7 +669,7 @@ def run_holdout(args):
                 f = rot.mats[0].features
                 sel = dg.dgsp_algo_name(dg.dgsp_select_algo(f, n))
                 best = min(table, key=table.get)
-                rec = {"matrix": name, "N": n, "avg_row": f.avg_row, "cv_row": f.cv_row, "max_row": f.max_row, "nnz": A.nnz,
+                rec = {"matrix": name, "N": n, "M": A.M, "avg_row": f.avg_row, "cv_row": f.cv_row, "max_row": f.max_row, "nnz": A.nnz,
                        "K": A.K, "col_span": f.col_span, "ms": table, "selected": sel, "best": best,
                        "loss": table[sel] / table[best] - 1.0}
                 cells.append(rec)
@@ -688,98 +688,134 @@ def run_holdout(args):
 
 THRESHOLD_NAMES = ("n_parallel_max", "pr_avg_row_min", "pr_cv_max", "sr_cv_min", "sr_stdv_min", "pr_nnz_max",
                    "short_avg_row_max", "short_max_row_max", "wide_parallel_n", "big_x_bytes_min", "big_x_cv_max",
-                   "big_x_avg_row_max")
+                   "big_x_avg_row_max", "short_min_waves", "pr_small_nnz_max", "pr_small_cv_max")
+
+
+def sr_lanes(N):
+    """Lanes per row of the sequential kernels at width N (a power of two covering N in lanes of four columns)."""
+    if N < 4:
+        return 1
+    g = 1
+    while g < (N + 3) // 4:
+        g *= 2
+    return min(g, 64)
+
+
+def rules_choose(r, t):
+    """The library's selection rules (dgsp_select_algo) on a bench record r with thresholds t (a dict)."""
+    N = r["N"]
+    M = r.get("M") or (round(r["nnz"] / r["avg_row"]) if r["avg_row"] > 0 else 0)
+    if (r["nnz"] > 0 and r["avg_row"] <= t["short_avg_row_max"] and r["max_row"] <= t["short_max_row_max"]
+            and M * sr_lanes(N) >= 64 * t["short_min_waves"]):
+        return "rs_sr"
+    if N <= t["n_parallel_max"]:
+        if (t["big_x_bytes_min"] > 0 and r.get("K", 0) * N * 4 >= t["big_x_bytes_min"] and r["cv_row"] <= t["big_x_cv_max"]
+                and r["avg_row"] <= t["big_x_avg_row_max"] and r.get("col_span", 0.0) >= 0.5):
+            return "rs_sr"
+        if 0 < r["nnz"] <= t["pr_small_nnz_max"] and r["cv_row"] <= t["pr_small_cv_max"]:
+            return "rs_pr"
+        row_split = r["avg_row"] >= t["pr_avg_row_min"] and r["cv_row"] <= t["pr_cv_max"] and r["nnz"] < t["pr_nnz_max"]
+        return "rs_pr" if row_split else "nb_pr"
+    if not (r["cv_row"] > t["sr_cv_min"] and r["avg_row"] * r["cv_row"] > t["sr_stdv_min"]):
+        return "rs_sr"
+    return "nb_pr" if N <= t["wide_parallel_n"] else "nb_sr"
 
 
 def run_fit(args):
     """Grid-fits the selector thresholds.  Data: the seed-0 matrices of a finished sweep
     (bench_sweep.jsonl under RESULTS_DIR) plus, if that suite ran, the larger matrices of
-    bench_size.jsonl (the sweep alone cannot place the size guard); checked on the
-    seed-1 matrices of the sweep.  No GPU needed."""
+    bench_size.jsonl (the sweep alone cannot place the size guards); checked on the
+    seed-1 matrices of the sweep and, if that suite ran, scored on bench_holdout.jsonl.  No GPU needed."""
     path = args.out or os.path.join(RESULTS_DIR, "bench_sweep.jsonl")
     rows = [json.loads(l) for l in open(path)]
-    size_path = os.path.join(os.path.dirname(path) or ".", "bench_size.jsonl")
-    big = [json.loads(l) for l in open(size_path)] if os.path.exists(size_path) else []
-    for r in rows + big:
-        r["stdv"] = r["avg_row"] * r["cv_row"]
-    inf = float("inf")
+    here = os.path.dirname(path) or "."
 
-    def choose(r, t):
-        npm, pr_avg, pr_cv, sr_cv, sr_std, nnz_max, sh_avg, sh_max, wide, bx_bytes, bx_cv, bx_avg = t
-        if r["avg_row"] <= sh_avg and r["max_row"] <= sh_max:
-            return "rs_sr"
-        if r["N"] <= npm:
-            if (bx_bytes > 0 and r.get("K", 0) * r["N"] * 4 >= bx_bytes and r["cv_row"] <= bx_cv
-                    and r["avg_row"] <= bx_avg and r.get("col_span", 0.0) >= 0.5):
-                return "rs_sr"
-            return "rs_pr" if (r["avg_row"] >= pr_avg and r["cv_row"] <= pr_cv and r["nnz"] < nnz_max) else "nb_pr"
-        if not (r["cv_row"] > sr_cv and r["stdv"] > sr_std):
-            return "rs_sr"
-        return "nb_pr" if r["N"] <= wide else "nb_sr"
+    def load(name):
+        f = os.path.join(here, name)
+        return [json.loads(l) for l in open(f)] if os.path.exists(f) else []
+
+    big, hold = load("bench_size.jsonl"), load("bench_holdout.jsonl")
+    inf = float("inf")
+    off = dict(pr_nnz_max=inf, short_avg_row_max=0.0, short_max_row_max=0, wide_parallel_n=0, big_x_bytes_min=0,
+               big_x_cv_max=0.0, big_x_avg_row_max=0.0, short_min_waves=0, pr_small_nnz_max=0, pr_small_cv_max=0.0)
+
+    def losses(rs, t):
+        return [r["ms"][rules_choose(r, t)] / min(r["ms"].values()) - 1 for r in rs]
 
     def loss(rs, t):
-        if not rs:
-            return 0.0, 0.0
-        l = [r["ms"][choose(r, t)] / min(r["ms"].values()) - 1 for r in rs]
-        return sum(l) / len(l), max(l)
+        l = losses(rs, t)
+        return (sum(l) / len(l), max(l)) if l else (0.0, 0.0)
 
     fit = [r for r in rows if r["matrix"].endswith("_s0")]
     test = [r for r in rows if r["matrix"].endswith("_s1")]
     train = fit + big
 
     # stage 1: the paper's tree (5 thresholds), added rules off; stage 2: the added rules on the 20 best trees
-    tree = [(npm, a, c, sc, ss) for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
+    tree = [dict(off, n_parallel_max=npm, pr_avg_row_min=a, pr_cv_max=c, sr_cv_min=sc, sr_stdv_min=ss)
+            for npm in (1, 2, 4, 8) for a in (0, 2, 8, 12, 24, 48, 1e9)
             for c in (0.05, 0.1, 0.2, 0.3, 0.5, 1.0, 2.0, 4.0, 1e30) for sc in (0.3, 0.8, 1.0, 1.5, 2.0, 3.5, 1e9)
             for ss in (0, 3, 10, 30, 60)]
-    off = (inf, 0.0, 0, 0, 0, 0.0, 0.0)
-    nobx = (0, 0.0, 0.0)
-    ranked = sorted(tree, key=lambda t: loss(train, t + off)[0])
-    added = [(nm, a, m, w) for nm in (5e6, 1e7, 2e7, 4e7, inf) for (a, m) in
-             [(0.0, 0)] + [(a, m) for a in (5, 10, 20, 40) for m in (16, 32, 64, 128, 512)] for w in (0, 8)]
-    best = min((t + x + nobx for t in ranked[:20] for x in added), key=lambda t: loss(train, t)[0])
-    # stage 3: the large-dense-operand rule on top (it needs K and col_span in the records)
-    bigx = [nobx] + [(b, c, a) for b in (4.2e6, 6e6, 1.2e7) for c in (0.05, 0.2, 0.3) for a in (48, 64, 128)]
-    best = min((best[:9] + x for x in bigx), key=lambda t: loss(train, t)[0])
+    ranked = sorted(tree, key=lambda t: loss(train, t)[0])
+    added = [dict(pr_nnz_max=nm, short_avg_row_max=a, short_max_row_max=m, wide_parallel_n=w)
+             for nm in (5e6, 1e7, 2e7, 4e7, inf)
+             for (a, m) in [(0.0, 0)] + [(a, m) for a in (5, 10, 20, 40) for m in (16, 32, 64, 128, 512)] for w in (0, 8)]
+    best = min((dict(t, **x) for t in ranked[:20] for x in added), key=lambda t: loss(train, t)[0])
+    # stage 3: the large-dense-operand rule; stage 4: the row-count condition of the short-row rule and the
+    # small-matrix rule of the parallel side
+    bigx = [dict()] + [dict(big_x_bytes_min=b, big_x_cv_max=c, big_x_avg_row_max=a)
+                       for b in (4.2e6, 6e6, 1.2e7) for c in (0.05, 0.2, 0.3) for a in (48, 64, 128)]
+    best = min((dict(best, **x) for x in bigx), key=lambda t: loss(train, t)[0])
+    small = [dict(short_min_waves=w, pr_small_nnz_max=n, pr_small_cv_max=c)
+             for w in (0, 1024, 2048, 4096) for n in (0, 2e6, 4e6, 8e6) for c in (0.15, 0.3, 0.6)]
+    best = min((dict(best, **x) for x in small), key=lambda t: loss(train, t)[0])
     grid_best = best
     # what is reported below is what ships: the library's defaults (the grid's optimum beside them; the loss is
     # flat in several thresholds, so the two differ without one being better)
     try:
         from paper_2106_16064_amd import binding as dg
         d = dg.dgsp_get_thresholds()
-        best = tuple(getattr(d, k) for k in THRESHOLD_NAMES)
+        best = {k: getattr(d, k) for k in THRESHOLD_NAMES}
         shipped = True
     except Exception:            # no library built: report the grid's optimum
         shipped = False
-    paper = min((t + off for t in tree if t[0] == 4 and t[2] == 1e30 and t[4] == 0), key=lambda t: loss(fit, t)[0])
+    paper = min((t for t in tree if t["n_parallel_max"] == 4 and t["pr_cv_max"] == 1e30 and t["sr_stdv_min"] == 0),
+                key=lambda t: loss(fit, t)[0])
     single = {k: (sum(r["ms"][k] / min(r["ms"].values()) - 1 for r in rows) / len(rows)) for k in rows[0]["ms"]}
     per_n = {}
-    for r in rows:
-        per_n.setdefault(r["N"], []).append(r["ms"][choose(r, best)] / min(r["ms"].values()) - 1)
+    for r, l in zip(rows, losses(rows, best)):
+        per_n.setdefault(r["N"], []).append(l)
 
-    def variant(**kw):            # the fitted thresholds with some of the added rules switched off
-        t = dict(zip(THRESHOLD_NAMES, best))
-        t.update(kw)
-        t = tuple(t[k] for k in THRESHOLD_NAMES)
-        return {"sweep_fit": loss(fit, t)[0], "sweep_heldout": loss(test, t)[0], "size_cells": loss(big, t)[0]}
+    def variant(**kw):            # the shipped thresholds with some of the added rules switched off
+        t = dict(best, **kw)
+        return {"sweep_fit": loss(fit, t)[0], "sweep_heldout": loss(test, t)[0], "size_cells": loss(big, t)[0],
+                "holdout_cells": loss(hold, t)[0]}
+
+    def over(rs, t, limit=0.10):
+        return [{"matrix": r["matrix"], "N": r["N"], "selected": rules_choose(r, t), "best": min(r["ms"], key=r["ms"].get),
+                 "loss": round(l, 3)} for r, l in zip(rs, losses(rs, t)) if l > limit]
 
     print(json.dumps({
-        "suite": "fit", "sweep_cells": len(rows), "size_cells": len(big),
-        "thresholds": dict(zip(THRESHOLD_NAMES, best)), "thresholds_are_library_defaults": shipped,
-        "grid_fit": {"thresholds": dict(zip(THRESHOLD_NAMES, grid_best)), "sweep_fit": loss(fit, grid_best)[0],
+        "suite": "fit", "sweep_cells": len(rows), "size_cells": len(big), "holdout_cells": len(hold),
+        "thresholds": best, "thresholds_are_library_defaults": shipped,
+        "grid_fit": {"thresholds": grid_best, "sweep_fit": loss(fit, grid_best)[0],
                      "sweep_heldout": loss(test, grid_best)[0], "size_cells": loss(big, grid_best)[0]},
         "mean_loss_fit_seed0": loss(fit, best)[0], "mean_loss_heldout_seed1": loss(test, best)[0],
         "mean_loss_sweep_all": loss(rows, best)[0], "max_loss_sweep_all": loss(rows, best)[1],
-        "geomean_loss_sweep_all": math.exp(sum(math.log(r["ms"][choose(r, best)] / min(r["ms"].values())) for r in rows)
-                                           / len(rows)) - 1.0,
+        "geomean_loss_sweep_all": math.exp(sum(math.log1p(l) for l in losses(rows, best)) / len(rows)) - 1.0,
         "mean_loss_size_cells": loss(big, best)[0], "max_loss_size_cells": loss(big, best)[1],
+        "holdout": {"mean_loss": loss(hold, best)[0], "worst_loss": loss(hold, best)[1],
+                    "cells_over_10pct": len(over(hold, best)), "over_10pct": over(hold, best)},
+        "over_10pct_sweep": over(rows, best), "over_10pct_size": over(big, best),
         "added_rules_off": {"no_short_row_rule": variant(short_avg_row_max=0.0, short_max_row_max=0),
+                            "short_rows_at_any_row_count": variant(short_min_waves=0),
+                            "no_small_matrix_rule": variant(pr_small_nnz_max=0),
                             "no_size_guard": variant(pr_nnz_max=inf),
                             "no_eight_column_rule": variant(wide_parallel_n=0),
                             "no_large_x_rule": variant(big_x_bytes_min=0),
-                            "none": variant(short_avg_row_max=0.0, short_max_row_max=0, pr_nnz_max=inf,
-                                            wide_parallel_n=0, big_x_bytes_min=0)},
-        "paper_shaped_tree": {"thresholds": dict(zip(THRESHOLD_NAMES, paper)), "mean_loss_fit": loss(fit, paper)[0],
-                              "mean_loss_heldout": loss(test, paper)[0], "mean_loss_size_cells": loss(big, paper)[0]},
+                            "none": variant(**off)},
+        "paper_shaped_tree": {"thresholds": paper, "mean_loss_fit": loss(fit, paper)[0],
+                              "mean_loss_heldout": loss(test, paper)[0], "mean_loss_size_cells": loss(big, paper)[0],
+                              "mean_loss_holdout_cells": loss(hold, paper)[0]},
         "always_one_kernel_mean_loss": single,
         "mean_loss_per_N": {str(n): sum(v) / len(v) for n, v in sorted(per_n.items())}}))
     return 0

@@ -103,7 +103,18 @@ typedef struct {
  *              sequential.  When no row is long, one lane group per row keeps the
  *              whole wave busy for max_row steps with no cross-lane step and no
  *              long-row tail; it beat the other three kernels on every such
- *              matrix measured.  Set short_avg_row_max to 0 to switch it off.
+ *              matrix measured with enough rows.  It applies only when the rows fill the
+ *              machine: the row-split sequential kernel runs M * (lanes per row at this N)
+ *              / 64 waves, and with fewer than short_min_waves of them (65 536 rows at
+ *              N <= 4 are 1024 waves) most CUs hold a single wave; such matrices go on to
+ *              the rules below.  Set short_avg_row_max to 0 to switch the rule off,
+ *              short_min_waves to 0 to apply it at any size.
+ *   small matrix, parallel side (an addition): N <= n_parallel_max AND nnz <=
+ *              pr_small_nnz_max AND cv_row <= pr_small_cv_max -> row-split parallel.  The
+ *              balanced kernels need a second, small launch (4-6 us); for a matrix whose
+ *              whole multiplication takes 12-20 us the single launch wins when no row is
+ *              much longer than the others (27-point stencil on 40^3: 12-14 against
+ *              19-20 us).  pr_small_nnz_max 0 switches it off.
  *   large dense operand (an addition, checked second, on the parallel side
  *              N <= n_parallel_max only): K * N * 4 >= big_x_bytes_min AND
  *              cv_row <= big_x_cv_max AND avg_row <= big_x_avg_row_max AND
@@ -127,6 +138,9 @@ typedef struct {
     int64_t big_x_bytes_min;
     double big_x_cv_max;
     double big_x_avg_row_max;
+    int64_t short_min_waves;
+    int64_t pr_small_nnz_max;
+    double pr_small_cv_max;
 } dgsp_thresholds_t;
 
 /*

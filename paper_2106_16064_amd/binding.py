@@ -49,7 +49,9 @@ class Thresholds(ctypes.Structure):
                 ("sr_stdv_min", ctypes.c_double), ("pr_nnz_max", ctypes.c_int64),
                 ("short_avg_row_max", ctypes.c_double), ("short_max_row_max", ctypes.c_int64),
                 ("wide_parallel_n", ctypes.c_int64), ("big_x_bytes_min", ctypes.c_int64),
-                ("big_x_cv_max", ctypes.c_double), ("big_x_avg_row_max", ctypes.c_double)]
+                ("big_x_cv_max", ctypes.c_double), ("big_x_avg_row_max", ctypes.c_double),
+                ("short_min_waves", ctypes.c_int64), ("pr_small_nnz_max", ctypes.c_int64),
+                ("pr_small_cv_max", ctypes.c_double)]
 
 
 class DgspError(RuntimeError):

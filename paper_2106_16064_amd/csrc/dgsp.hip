@@ -399,7 +399,18 @@ int launch_nb_sr_v(const Problem& p) {
     // the same chunks, one after the other in launch order.  The rows of X that many matrix rows share (hub
     // columns of a power-law graph) then compete for the L2 with a quarter-kilobyte each instead of N * 4
     // bytes; re-reading the 8 bytes of an entry per block costs 3 % of what the block gathers for it.
-    const SrColumns cols = sr_columns(p.N, V, p.N >= 128);
+    SrColumns cols = sr_columns(p.N, V, p.N >= 128);
+    // A matrix with fewer tiles than the machine has room for waves (two per SIMD) leaves CUs idle: a wave takes a
+    // whole tile of 512 items whatever N is.  Narrower column blocks make more workgroups out of the same tiles
+    // (65 536 rows of 4 entries at N = 32: 640 tiles on 1024 SIMDs; two blocks of 16 columns instead of one of 32).
+    if (p.nnz >= 0) {
+        const long long tiles = (p.nnz + (long long)p.M + kNbSrTile - 1) / kNbSrTile;
+        const long long room = (long long)device_info().cus * kWavesPerBlock * 2;
+        while (tiles * cols.blocks < room && cols.logG > 0 && cols.cols_per_block % (2 * V) == 0) {
+            const int per = cols.cols_per_block / 2;
+            cols = SrColumns{sr_lanes_log2(per, V), per, (unsigned)((p.N + per - 1) / per)};
+        }
+    }
     const int logG = cols.logG;
     const unsigned col_blocks = cols.blocks;
     if (col_blocks > 65535u) return DGSP_ERR_INVALID_ARG;
@@ -455,6 +466,9 @@ dgsp_thresholds_t g_thresholds = {
     /* big_x_bytes_min   */ 6000000,
     /* big_x_cv_max      */ 0.2,
     /* big_x_avg_row_max */ 64.0,
+    /* short_min_waves   */ 2048,
+    /* pr_small_nnz_max  */ 2000000,
+    /* pr_small_cv_max   */ 0.6,
 };
 
 dgsp_thresholds_t thresholds_snapshot() {
@@ -640,13 +654,19 @@ extern "C" int dgsp_spmm_csr_i64(int64_t M, int64_t K, int64_t N, int64_t nnz, c
 extern "C" int dgsp_select_algo(const dgsp_features_t* f, int64_t N) {
     if (!f || N < 1) return DGSP_AUTO;
     const dgsp_thresholds_t t = thresholds_snapshot();
-    // all rows short: one lane group per row keeps a wave busy with no cross-lane step and no idle tail
-    if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) return DGSP_RS_SR;
+    // all rows short: one lane group per row keeps a wave busy with no cross-lane step and no idle tail - provided
+    // the rows fill the machine: the row-split sequential kernel runs M * (lanes per row) / 64 waves
+    if (f->nnz > 0 && f->avg_row <= t.short_avg_row_max && f->max_row <= t.short_max_row_max) {
+        const int lanes_log2 = N < 4 ? 0 : sr_lanes_log2(N, 4);
+        if ((double)f->M * (double)(1 << lanes_log2) >= 64.0 * (double)t.short_min_waves) return DGSP_RS_SR;
+    }
     if (N <= t.n_parallel_max) {
         // X beyond one L2, rows alike and spread over all columns: one row per lane sweeps X in step
         if (t.big_x_bytes_min > 0 && (double)f->K * (double)N * 4.0 >= (double)t.big_x_bytes_min &&
             f->cv_row <= t.big_x_cv_max && f->avg_row <= t.big_x_avg_row_max && f->col_span >= 0.5)
             return DGSP_RS_SR;
+        // a small matrix of about equal rows: the balanced kernel's second launch (4-6 us) is a third of the call
+        if (f->nnz > 0 && f->nnz <= t.pr_small_nnz_max && f->cv_row <= t.pr_small_cv_max) return DGSP_RS_PR;
         // parallel reduction: long rows keep a row's lanes busy, short rows idle them
         const bool row_split = f->avg_row >= t.pr_avg_row_min && f->cv_row <= t.pr_cv_max && f->nnz < t.pr_nnz_max;
         return row_split ? DGSP_RS_PR : DGSP_NB_PR;

@@ -73,7 +73,7 @@ def test_selection_rules_follow_the_decision_tree():
     stdv_row/avg_row (sequential side) decide whether to balance."""
     saved = dg.dgsp_get_thresholds()
     try:
-        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0, 0, 0, 0.0, 0.0)   # the paper's rule verbatim (no added guards)
+        t = dg.Thresholds(4, 32.0, 1e30, 1.0, 0.0, 2**62, 0.0, 0, 0, 0, 0.0, 0.0, 0, 0, 0.0)   # the paper's rule verbatim (no added guards)
         dg.dgsp_set_thresholds(t)
         got = dg.dgsp_get_thresholds()
         assert (got.n_parallel_max, got.pr_avg_row_min, got.sr_cv_min) == (4, 32.0, 1.0)
@@ -130,6 +130,23 @@ def test_selection_rules_follow_the_decision_tree():
         assert dg.dgsp_select_algo(f, 4) == dg.NB_PR                       # uneven rows
         f = feat(100, 0.1, M=1 << 20); f.col_span = 0.9
         assert dg.dgsp_select_algo(f, 4) == dg.RS_PR                       # long rows: the tree's parallel side
+        t.short_min_waves = 2048                                           # short rows need enough of them
+        dg.dgsp_set_thresholds(t)
+        f = feat(4, 0.5, M=1 << 18); f.max_row = 16
+        assert dg.dgsp_select_algo(f, 2) == dg.RS_SR                       # 4096 waves of one row per lane
+        f = feat(4, 0.5, M=1 << 16); f.max_row = 16
+        assert dg.dgsp_select_algo(f, 2) == dg.NB_PR                       # 1024 waves: back to the tree
+        assert dg.dgsp_select_algo(f, 32) == dg.RS_SR                      # eight lanes per row: 8192 waves
+        t.pr_small_nnz_max, t.pr_small_cv_max = 2_000_000, 0.6             # the added small-matrix rule
+        dg.dgsp_set_thresholds(t)
+        assert dg.dgsp_select_algo(f, 2) == dg.RS_PR                       # 262 144 entries, rows about alike
+        f = feat(26, 0.13, M=64000); f.max_row = 27
+        assert dg.dgsp_select_algo(f, 1) == dg.RS_PR and dg.dgsp_select_algo(f, 4) == dg.RS_PR
+        assert dg.dgsp_select_algo(f, 8) == dg.RS_SR                       # sequential side unaffected
+        f = feat(26, 2.0, M=64000)
+        assert dg.dgsp_select_algo(f, 1) == dg.NB_PR                       # uneven rows stay balanced
+        f = feat(26, 0.13, M=1 << 20); f.col_span = 0.01
+        assert dg.dgsp_select_algo(f, 1) == dg.NB_PR                       # 27 million entries: the second launch pays
         L = dg.lib()
         assert L.dgsp_select_algo(None, 4) == dg.AUTO
         assert dg.dgsp_select_algo(feat(4, 1), 0) == dg.AUTO
@@ -197,6 +214,11 @@ def test_default_thresholds_and_their_effect_on_benchmark_shapes():
     E = wl.sweep_csr(1 << 12, 27, "fixed", 0)
     f = dg.dgsp_features_from_csr_host(E.M, E.K, E.rowptr, E.colidx)
     assert f.cv_row == 0.0 and f.col_span > 0.8
+    assert dg.dgsp_select_algo(f, 4) == dg.RS_PR        # 110 592 entries of equal rows: a small matrix, one launch
+    f.nnz = 27 << 20                                    # as many rows as the size study's: the tree decides
     assert dg.dgsp_select_algo(f, 4) == dg.NB_PR        # 4096 columns: X is 64 KB
     f.K = 1 << 20                                       # the same rows over 2^20 columns: X is 16 MB at N = 4
     assert dg.dgsp_select_algo(f, 4) == dg.RS_SR and dg.dgsp_select_algo(f, 1) == dg.NB_PR
+    small = wl.stencil27_csr(24)                        # 13 824 rows: short of rows for one lane per row
+    f = dg.dgsp_features_from_csr_host(small.M, small.K, small.rowptr, small.colidx)
+    assert [dg.dgsp_select_algo(f, n) for n in (1, 4, 8)] == [dg.RS_PR, dg.RS_PR, dg.RS_SR]
