@@ -23,6 +23,7 @@ and writes its per-cell records under RESULTS_DIR):
     --suite fit       fits the selector thresholds on a finished sweep (no GPU)
     --suite widths    the adaptive call at 34 dense widths from 1 to 128 on three matrices
     --suite holdout   the shipped selection rules scored on matrices they were not fitted on
+    --suite layouts   the balanced sequential kernel's wide-N column layouts on the GNN configuration
 """
 from __future__ import annotations
 
@@ -599,6 +600,7 @@ def run_ablation(args):
                     # the third alternative of Section 2.1.1: balanced, segment reduction as a serial scan
                     row["spmv_ms"]["nb_pr_serial_scan"] = med(lambda i: rot.ablation(i, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN))
                     row["spmv_ms"]["nb_pr_item_tiles"] = med(lambda i: rot.ablation(i, dg.NB_PR, dg.ABL_ITEM_TILES))
+                    row["spmv_ms"]["nb_pr_entry_blocks"] = med(lambda i: rot.ablation(i, dg.NB_PR, dg.ABL_ENTRY_BLOCKS))
                     del rot
                     rot = Rotation(A, wl.dense_matrix(A.K, 2, "uniform", seed=0))
                     row["n2_ms"] = {}
@@ -627,17 +629,49 @@ def run_ablation(args):
         four = {k: r["spmv_ms"][k] for k in ("rs_sr", "rs_pr", "nb_sr", "nb_pr")}
         b = min(four, key=four.get)
         wins[b] = wins.get(b, 0) + 1
-        d = min(points, key=lambda k: r["spmv_ms"][k])
+        d = min(points, key=lambda k: r["spmv_ms"][k if k != "nb_pr" else "nb_pr_entry_blocks"])
         design[d] = design.get(d, 0) + 1
     print(json.dumps({
         "suite": "ablation", "matrices": len(rows), "file": path,
         "spmv_best_kernel_counts": wins,
         "spmv_design_points_best_counts": design,
-        "segment_scan_dpp_vs_serial_speedup_N1": geomean([r["spmv_ms"]["nb_pr_serial_scan"] / r["spmv_ms"]["nb_pr"] for r in rows]),
-        "entry_blocks_vs_item_tiles_speedup_N1": geomean([r["spmv_ms"]["nb_pr_item_tiles"] / r["spmv_ms"]["nb_pr"] for r in rows]),
+        "segment_scan_dpp_vs_serial_speedup_N1": geomean([r["spmv_ms"]["nb_pr_serial_scan"] / r["spmv_ms"]["nb_pr_entry_blocks"] for r in rows]),
+        "entry_blocks_vs_item_tiles_speedup_N1": geomean([r["spmv_ms"]["nb_pr_item_tiles"] / r["spmv_ms"]["nb_pr_entry_blocks"] for r in rows]),
+        "entry_blocks_vs_item_tiles_speedup_N1_from_6M_entries": geomean(
+            [r["spmv_ms"]["nb_pr_item_tiles"] / r["spmv_ms"]["nb_pr_entry_blocks"] for r in rows if r["nnz"] >= 6e6] or [1.0]),
         "vector_dense_loads_speedup_N2": {a: geomean([r["n2_ms"][a + "_scalar_loads"] / r["n2_ms"][a] for r in rows])
                                           for a in ("rs_pr", "nb_pr")},
         "sparse_staging_speedup_N128": geomean([r["n128_ms"]["rs_sr_no_staging"] / r["n128_ms"]["rs_sr"] for r in rows])}))
+    return 0
+
+
+def run_layouts(args):
+    """The wide-N layouts of the balanced sequential kernel on the GNN-style configuration (R-MAT 2^20, row-normalised,
+    N = 64, 128 and 256) and on a matrix with uniform columns: column blocks of 64 (what ships) or 32, tied to XCDs
+    (what ships from N = 128 on) or not; whole call, event-timed, for the comparison table under profiles/."""
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_layouts.jsonl")
+    variants = {"blocks_of_64_on_xcds (ships at N >= 128)": 0, "blocks_of_64_any_xcd": dg.ABL_BLOCKS_OFF_XCDS,
+                "blocks_of_32_on_xcds": dg.ABL_COLUMN_BLOCKS_32,
+                "blocks_of_32_any_xcd": dg.ABL_COLUMN_BLOCKS_32 | dg.ABL_BLOCKS_OFF_XCDS}
+    cells = 0
+    with open(path, "w") as fh:
+        for name in ("rmat_gnn", "uniform64"):
+            for n in (64, 128, 256):
+                A, X, label = make_workload(name, n)
+                rot = Rotation(A, X)
+                rec = {"workload": label, "N": n, "nnz": A.nnz, "algorithmic_bytes": algorithmic_bytes(A, n), "us": {}}
+                for vname, sw in variants.items():
+                    ms = time_events(None, lambda i: rot.ablation(i, dg.NB_SR, sw), max(8, min(args.steps, 20)), 3)
+                    rec["us"][vname] = median(ms) * 1e3
+                fh.write(json.dumps(rec) + "\n")
+                fh.flush()
+                cells += 1
+                print(f"[layouts] {label}: " + ", ".join(f"{k} {v:.0f} us" for k, v in rec["us"].items()), file=sys.stderr, flush=True)
+                del rot
+    print(json.dumps({"suite": "layouts", "cells": cells, "file": path}))
     return 0
 
 
@@ -846,7 +880,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths", "holdout"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths", "holdout", "layouts"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -872,7 +906,7 @@ def main():
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
             "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel, "widths": run_widths,
-            "holdout": run_holdout}[args.suite](args)
+            "holdout": run_holdout, "layouts": run_layouts}[args.suite](args)
 
 
 if __name__ == "__main__":

@@ -381,11 +381,15 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                DGSP_ERR_UNSUPPORTED.
  *   DGSP_ABL_ITEM_TILES          the balanced parallel kernel with its chunks cut into tiles of
  *                                merge-path items (entries + row ends), where a tile's gathers can
- *                                only be requested after the previous tile's row ends are counted;
- *                                DGSP_NB_PR runs blocks of entries instead, whose addresses are known
- *                                ahead, and keeps the next block's gathers in flight during the row
- *                                logic.  The comparison for that design choice.  Only DGSP_NB_PR,
- *                                else DGSP_ERR_UNSUPPORTED.
+ *                                only be requested after the previous tile's row ends are counted.
+ *   DGSP_ABL_ENTRY_BLOCKS        the balanced parallel kernel walking blocks of entries instead, whose
+ *                                addresses are known ahead, with the next block's gathers in flight during
+ *                                the row logic.  DGSP_NB_PR itself takes entry blocks at one or two dense
+ *                                columns per lane from six million entries on and item tiles otherwise;
+ *                                the two switches force one or the other: the comparison for that choice.
+ *                                Only DGSP_NB_PR (entry blocks: only at widths that run one or two columns
+ *                                per lane, see DGSP_ABL_SERIAL_SEGMENT_SCAN), not both, else
+ *                                DGSP_ERR_UNSUPPORTED.
  *   DGSP_ABL_SERIAL_SEGMENT_SCAN the balanced parallel kernel with its segment reduction done as a serial
  *                                scan: the lanes' partial sums go to LDS and one lane adds them up in order,
  *                                starting afresh at every row boundary.  Same balanced split, same loads: the
@@ -395,7 +399,18 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                DGSP_RS_PR).  Only DGSP_NB_PR at widths that run one or two dense columns per
  *                                lane (N = 1, 2, other N that 3 and 4 do not divide, or any N together with
  *                                DGSP_ABL_SCALAR_DENSE_LOADS), not with DGSP_ABL_ITEM_TILES; else
- *                                DGSP_ERR_UNSUPPORTED.
+ *                                DGSP_ERR_UNSUPPORTED.  It runs on the entry-block pipeline at any size, so
+ *                                it is to be held against DGSP_ABL_ENTRY_BLOCKS.
+ *   DGSP_ABL_COLUMN_BLOCKS_32    the balanced sequential kernel with column blocks of 32 dense columns (one
+ *                                128-byte line of a row of X per entry and block) instead of 64, where N is a
+ *                                multiple of 32 from 64 on (ignored elsewhere): more passes over the sparse
+ *                                matrix against a smaller slice of X per pass.
+ *   DGSP_ABL_BLOCKS_OFF_XCDS     the balanced sequential kernel with its column blocks as a second grid
+ *                                dimension, any XCD taking any block.  DGSP_NB_SR itself, when N >= 128 makes
+ *                                2, 4 or 8 column blocks, lets every XCD work on one block only, so that an L2
+ *                                sees one block's slice of X.  Both switches are comparisons for the layout
+ *                                of the wide-N path (Section 2.1.3's kernel at N >= 64) and only go with
+ *                                DGSP_NB_SR, else DGSP_ERR_UNSUPPORTED.
  * Unknown bits -> DGSP_ERR_INVALID_ARG.  algo must be one of the four kernels.
  * `features` may be NULL (host pointer otherwise; nnz and col_span are used).
  */
@@ -403,6 +418,9 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
 #define DGSP_ABL_NO_SPARSE_STAGING 2
 #define DGSP_ABL_ITEM_TILES 4
 #define DGSP_ABL_SERIAL_SEGMENT_SCAN 8
+#define DGSP_ABL_COLUMN_BLOCKS_32 16
+#define DGSP_ABL_BLOCKS_OFF_XCDS 32
+#define DGSP_ABL_ENTRY_BLOCKS 64
 int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t nnz,
                            const int32_t *rowptr, const int32_t *colidx, const float *vals,
                            const float *X, float *Y, int algo, int switches,

@@ -28,6 +28,7 @@ EXPORTS = (
 )
 PHASE_ALL, PHASE_PREPARE, PHASE_MAIN = 0, 1, 2
 ABL_SCALAR_DENSE_LOADS, ABL_NO_SPARSE_STAGING, ABL_ITEM_TILES, ABL_SERIAL_SEGMENT_SCAN = 1, 2, 4, 8
+ABL_COLUMN_BLOCKS_32, ABL_BLOCKS_OFF_XCDS, ABL_ENTRY_BLOCKS = 16, 32, 64
 FEATURES_WORKSPACE_BYTES = 64
 PROBE_GATHER, PROBE_STREAM_GATHER_FMA, PROBE_ROW_GATHER = 0, 1, 2
 

@@ -343,13 +343,18 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
 }
 
 // Which pipeline the balanced parallel kernel runs.  Blocks of entries with the next block's gathers in flight
-// during the row logic (nb_pr_kernel) for one or two dense columns per lane: 8-9 % faster on power-law rows
-// (R-MAT 2^20: 98 -> 90 us at N = 1), even on the 27-point stencil.  From three columns on the registers that hold
-// a block's gathered values halve the resident waves (176 VGPRs at V = 4), which costs more than the overlap
-// gives (stencil N = 4: 150 -> 201 us), so those widths keep the tiles of merge-path items (nb_pr_tiled_kernel).
-// DGSP_ABL_ITEM_TILES forces the tiled pipeline everywhere (the comparison for this choice).
+// during the row logic (nb_pr_kernel) for one or two dense columns per lane on matrices of six million entries
+// and more: 2-6 % faster there on R-MAT matrices of every skew (2^20 vertices, degree 16, power law: 104 -> 98 us
+// per call, main launch 98 -> 90 us), even on the 27-point stencil.  Smaller matrices give a wave only a few
+// blocks, and the longer kernel's start-up costs more than the overlap returns (5-10 % slower from 0.25 to 4
+// million entries), so they keep the tiles of merge-path items (nb_pr_tiled_kernel), as does a call that does
+// not know its entry count.  From three columns per lane on the registers that hold a block's gathered values
+// halve the resident waves (176 VGPRs at V = 4), which costs more than the overlap gives (stencil N = 4:
+// 150 -> 201 us): tiles as well.  DGSP_ABL_ITEM_TILES / DGSP_ABL_ENTRY_BLOCKS force one or the other where both
+// exist (the comparison for this choice).
 template <int V>
 constexpr bool kNbPrStreams = V <= 2;
+constexpr long long kNbPrStreamNnzMin = 6000000;
 
 template <int V, int KQ>
 int launch_nb_pr_v(const Problem& p) {
@@ -357,7 +362,9 @@ int launch_nb_pr_v(const Problem& p) {
     const unsigned col_groups = (unsigned)((p.N + V - 1) / V);      // V = 8 also takes N = 5, 6, 7: one group
     // the row store addresses a step's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
-    const bool tiled = !kNbPrStreams<V> || (p.switches & DGSP_ABL_ITEM_TILES) != 0;
+    const bool forced_blocks = (p.switches & (DGSP_ABL_ENTRY_BLOCKS | DGSP_ABL_SERIAL_SEGMENT_SCAN)) != 0;
+    const bool tiled = !kNbPrStreams<V> || (p.switches & DGSP_ABL_ITEM_TILES) != 0 ||
+                       (!forced_blocks && p.nnz < kNbPrStreamNnzMin);          // unknown entry count (-1): tiles
     int resident = resident_blocks_per_cu(nb_pr_tiled_kernel<V, KQ>);
     if constexpr (kNbPrStreams<V>) { if (!tiled) resident = resident_blocks_per_cu(nb_pr_kernel<V, KQ>); }
     const dim3 grid(balanced_blocks(p, tile, resident, true), col_groups);
@@ -400,6 +407,9 @@ int launch_nb_sr_v(const Problem& p) {
     // columns of a power-law graph) then compete for the L2 with a quarter-kilobyte each instead of N * 4
     // bytes; re-reading the 8 bytes of an entry per block costs 3 % of what the block gathers for it.
     SrColumns cols = sr_columns(p.N, V, p.N >= 128);
+    // comparison: column blocks of 32 dense columns (one 128-byte line of a row of X per entry and block)
+    if ((p.switches & DGSP_ABL_COLUMN_BLOCKS_32) && V == 4 && p.N % 32 == 0 && p.N >= 64)
+        cols = SrColumns{3, 32, (unsigned)(p.N / 32)};
     // A matrix with fewer tiles than the machine has room for waves (two per SIMD) leaves CUs idle: a wave takes a
     // whole tile of 512 items whatever N is.  Narrower column blocks make more workgroups out of the same tiles
     // (65 536 rows of 4 entries at N = 32: 640 tiles on 1024 SIMDs; two blocks of 16 columns instead of one of 32).
@@ -417,16 +427,27 @@ int launch_nb_sr_v(const Problem& p) {
     const int logU = kNbSrLogTile - 6 + logG;   // items per lane-group run
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
     if (p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
-    const dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
+    dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
+    // Two, four or eight column blocks of a wide X (N >= 128): every XCD works on one block only, so that an L2 sees
+    // one block's slice of X and the slices do not compete (R-MAT 2^20 at N = 128: 1125 -> 1062 us; uniform columns:
+    // 1190 -> 1188 us).  The grid is then one-dimensional with whole workgroups per XCD.  DGSP_ABL_BLOCKS_OFF_XCDS
+    // keeps the blocks as a second grid dimension (the comparison).
+    unsigned pinned = 0;
+    if (!(p.switches & DGSP_ABL_BLOCKS_OFF_XCDS) && p.N >= 128 && (col_blocks == 2 || col_blocks == 4 || col_blocks == 8)) {
+        pinned = col_blocks;
+        const unsigned per_xcd = (grid.x * col_blocks + kXcd - 1) / kXcd;         // as many workgroups as before, in one dimension
+        grid = dim3(per_xcd * kXcd, 1);
+    }
+    const unsigned chunk_groups = pinned ? grid.x / pinned : grid.x;              // workgroups that share one chunk list
     if (p.phase != DGSP_PHASE_MAIN)
-        if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
+        if (int rc = launch_prepare(p, chunk_groups * kWavesPerBlock * kSubRanges, (unsigned)logU, kNbSrLogTile)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
         if (p.scaled) {
             DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH, true, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx,
-                        p.vals, p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta});
+                        p.vals, p.X, p.Y, logG, cols.cols_per_block, Scaling{p.alpha, p.beta}, pinned);
         } else {
             DGSP_LAUNCH((nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
-                        logG, cols.cols_per_block);
+                        logG, cols.cols_per_block, Scaling{1.0f, 0.0f}, pinned);
         }
     }
     return DGSP_OK;
@@ -571,8 +592,13 @@ extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t n
                                       const int32_t* colidx, const float* vals, const float* X, float* Y, int algo,
                                       int switches, const dgsp_features_t* features, void* stream) {
     if (algo < DGSP_RS_SR || algo > DGSP_NB_PR) return DGSP_ERR_INVALID_ARG;
-    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING | DGSP_ABL_ITEM_TILES | DGSP_ABL_SERIAL_SEGMENT_SCAN))
+    if (switches & ~(DGSP_ABL_SCALAR_DENSE_LOADS | DGSP_ABL_NO_SPARSE_STAGING | DGSP_ABL_ITEM_TILES | DGSP_ABL_SERIAL_SEGMENT_SCAN |
+                     DGSP_ABL_COLUMN_BLOCKS_32 | DGSP_ABL_BLOCKS_OFF_XCDS | DGSP_ABL_ENTRY_BLOCKS))
         return DGSP_ERR_INVALID_ARG;
+    if ((switches & DGSP_ABL_ENTRY_BLOCKS) &&
+        (algo != DGSP_NB_PR || (switches & DGSP_ABL_ITEM_TILES) || nb_pr_lane_width(N, switches) > 2))
+        return DGSP_ERR_UNSUPPORTED;
+    if ((switches & (DGSP_ABL_COLUMN_BLOCKS_32 | DGSP_ABL_BLOCKS_OFF_XCDS)) && algo != DGSP_NB_SR) return DGSP_ERR_UNSUPPORTED;
     if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
     if ((switches & DGSP_ABL_ITEM_TILES) && algo != DGSP_NB_PR) return DGSP_ERR_UNSUPPORTED;
     if (switches & DGSP_ABL_SERIAL_SEGMENT_SCAN) {

@@ -434,6 +434,12 @@ __device__ __forceinline__ ChunkPlan plan_chunks(const int* __restrict__ rowptr,
     return ChunkPlan(nnz, nnz + (unsigned)M, gridDim.x * kWavesPerBlock,
                      xcd_contiguous(blockIdx.x, gridDim.x) * kWavesPerBlock + wave_in_block(), quantum_log2);
 }
+// the same for a workgroup that is number `wg` of `nwg` sharing the list (a mapping of its own, see nb_sr_kernel)
+__device__ __forceinline__ ChunkPlan plan_chunks(const int* __restrict__ rowptr, int M, unsigned quantum_log2, unsigned wg,
+                                                 unsigned nwg) {
+    const unsigned nnz = (unsigned)rowptr[M];
+    return ChunkPlan(nnz, nnz + (unsigned)M, nwg * kWavesPerBlock, wg * kWavesPerBlock + wave_in_block(), quantum_log2);
+}
 
 // Number of rows whose end marker lies before diagonal d, i.e. rows r with
 // r + rowptr[r+1] < d (that key is strictly increasing in r).  64-way search,
@@ -1220,7 +1226,8 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
                                                         const int* __restrict__ colidx,
                                                         const float* __restrict__ vals,
                                                         const float* __restrict__ X, float* __restrict__ Y,
-                                                        int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f}) {
+                                                        int logG, int cols_per_block, Scaling sc = Scaling{1.0f, 0.0f},
+                                                        unsigned pinned_blocks = 0) {
     constexpr int W = kNbSrTile;
     constexpr int kStoreAux = V == 4 ? 2 : 0;           // results leave non-temporal when rows are 16 bytes or more per lane
     constexpr int kSlotFloats = 2 * kWave * V;          // (64/G + 1) slots of G*V floats each, G <= 64
@@ -1245,12 +1252,25 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const int groups = kWave >> logG;
     const int logU = kNbSrLogTile - 6 + logG;
     const unsigned U = 1u << logU;
-    const LaneColumns mine = lane_columns<V, RAGGED>(blockIdx.y, cols_per_block, gl, N);
+    // Column block and place in the chunk list.  Normally blockIdx.y is the column block and blockIdx.x (made
+    // XCD-contiguous) the place.  pinned_blocks = nb > 0 (a comparison, nb in {2, 4, 8}, gridDim = (8 k, 1)): the
+    // workgroups of XCD x all take column block x % nb, so that an L2 only ever sees one block's slice of X; the
+    // 8 / nb XCDs of a block share its chunk list, each a contiguous part.
+    unsigned col_block = blockIdx.y;
+    unsigned wg = 0, nwg = 0;
+    if (pinned_blocks) {
+        const unsigned x = blockIdx.x % kXcd, i = blockIdx.x / kXcd, per_xcd = gridDim.x / kXcd;
+        col_block = x % pinned_blocks;
+        wg = (x / pinned_blocks) * per_xcd + i;
+        nwg = (kXcd / pinned_blocks) * per_xcd;
+    }
+    const LaneColumns mine = lane_columns<V, RAGGED>(col_block, cols_per_block, gl, N);
     const long long n = mine.first;
     const bool col_ok = mine.any;
     const int tail = N % V;                  // columns of the lane that shares its window (RAGGED)
 
-    const ChunkPlan plan = plan_chunks(rowptr, M, (unsigned)logU);   // chunks start at multiples of U: runs stay aligned
+    // chunks start at multiples of U: runs stay aligned
+    const ChunkPlan plan = pinned_blocks ? plan_chunks(rowptr, M, (unsigned)logU, wg, nwg) : plan_chunks(rowptr, M, (unsigned)logU);
     const unsigned nnz = plan.nnz;
     const unsigned long long y_elems = dense_bytes(M, ldy, N) / 4ull;
     // XBUF: the dense operand is read through a descriptor (its byte offsets fit 32 bits)

@@ -412,12 +412,29 @@ def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
         A = wl.stencil27_csr(24, seed=34)
     X = wl.dense_matrix(A.K, N, "uniform", seed=35 + N)
     yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
-    for sw in (0, dg.ABL_ITEM_TILES, dg.ABL_SERIAL_SEGMENT_SCAN):
+    for sw in (0, dg.ABL_ITEM_TILES, dg.ABL_ENTRY_BLOCKS, dg.ABL_SERIAL_SEGMENT_SCAN):
         print(f"[case] nb_pr pipelines {kind} N={N} switches={sw}", flush=True)
         Y = _ablation_run(dg, A, X, dg.NB_PR, sw)
         assert not np.isnan(Y).any()
         ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
         assert ok, f"{kind} N={N} switches={sw}: worst |err|/bound = {worst:.3e}"
+        assert np.all(Y[A.row_lengths() == 0] == 0.0)
+
+
+@pytest.mark.parametrize("N", [32, 64, 128, 256])
+def test_wide_column_layouts_of_the_balanced_sequential_kernel(dg, N):
+    """Column blocks of 32 instead of 64 dense columns, and column blocks as a grid dimension instead of tied to
+    XCDs: comparison layouts of DGSP_NB_SR for wide X, same product (the shipped layout is what every other test of
+    the kernel at N >= 128 runs)."""
+    A = wl.rmat_csr(scale=14, avg_degree=16, seed=41)
+    X = wl.dense_matrix(A.K, N, "normal", seed=42)
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    for sw in (dg.ABL_COLUMN_BLOCKS_32, dg.ABL_BLOCKS_OFF_XCDS, dg.ABL_COLUMN_BLOCKS_32 | dg.ABL_BLOCKS_OFF_XCDS):
+        print(f"[case] nb_sr layouts N={N} switches={sw}", flush=True)
+        Y = _ablation_run(dg, A, X, dg.NB_SR, sw)
+        assert not np.isnan(Y).any()
+        ok, worst = oracle.within_bound(Y, yref, bnd, TOL)
+        assert ok, f"N={N} switches={sw}: worst |err|/bound = {worst:.3e}"
         assert np.all(Y[A.row_lengths() == 0] == 0.0)
 
 
@@ -429,12 +446,18 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     Y = torch.zeros((A.M, 2), device="cuda:0")
     L = dg.lib()
     args = (A.M, A.K, 2, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
+    # the same with N = 4 (refused before anything is launched, so the narrower X and Y do not matter)
+    args4 = (A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_NO_SPARSE_STAGING, None, None) == dg.ERR_UNSUPPORTED
-    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 64, None, None) == dg.ERR_INVALID_ARG
+    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 1 << 12, None, None) == dg.ERR_INVALID_ARG
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_PR, dg.ABL_SERIAL_SEGMENT_SCAN, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_COLUMN_BLOCKS_32, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_ENTRY_BLOCKS | dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args4, dg.NB_PR, dg.ABL_ENTRY_BLOCKS, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_ENTRY_BLOCKS, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, dg.ABL_BLOCKS_OFF_XCDS, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN | dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
-    args4 = (A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
     assert L.dgsp_spmm_csr_ablation(*args4, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.AUTO, 0, None, None) == dg.ERR_INVALID_ARG
     torch.cuda.synchronize()
