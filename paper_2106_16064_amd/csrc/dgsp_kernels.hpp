@@ -915,14 +915,17 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     const bool first_split = is < M && (unsigned)is + (unsigned)rowptr[is] < d0;
 
     // entries of block k of my chunk (lane l: entries 64 e + l of the block); nothing past the chunk's last entry
+    // One descriptor pair for the whole chunk (a wave's share of a matrix the library takes stays far below the
+    // 4 GB a descriptor spans); a block is a byte offset into it, kept in a VGPR and advanced by 4 W per block.
+    const unsigned long long chunk_bytes = ((unsigned long long)je1 - js0) * 4ull;
+    const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + js0, chunk_bytes);
+    const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + js0, chunk_bytes);
     auto load_entries = [&](unsigned k, int (&c)[E], float (&a)[E]) {
-        const unsigned long long from = (unsigned long long)js0 + (unsigned long long)k * W;
-        const unsigned long long bytes = from < je1 ? ((unsigned long long)je1 - from) * 4ull : 0ull;
-        const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + (bytes ? from : 0ull), bytes);
-        const __amdgpu_buffer_rsrc_t ra = make_buffer(vals + (bytes ? from : 0ull), bytes);
+        // past the chunk's last block every offset is out of range: nothing is loaded (k * W * 4 cannot wrap: k <= nb + 1)
+        const unsigned base = (unsigned long long)k * W * 4ull < chunk_bytes ? k * (unsigned)(W * 4) + (unsigned)lane * 4u : kOutOfRange;
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            const unsigned off = (unsigned)(e * kWave + lane) * 4u;
+            const unsigned off = base == kOutOfRange ? kOutOfRange : base + (unsigned)(e * kWave) * 4u;
             c[e] = (int)__builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 2);
             a[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra, off, 0, 2));
         }
@@ -932,17 +935,31 @@ __global__ __launch_bounds__(kBlock) void nb_pr_kernel(int M, long long K, int N
     const bool x_small = x_bytes <= 0xffffffffull;
     const __amdgpu_buffer_rsrc_t rx = make_buffer(X + n0, x_small ? x_bytes - (unsigned)n0 * 4ull : 0ull);
     // one vector gather per entry of block k, from the columns that load_entries(k) brought
+    // Entries past the chunk's end were loaded as column 0, value 0: their gathers read row 0 of X (in range: the
+    // matrix has entries, so K >= 1) and their products are masked, so the gathers need no mask of their own.
+    // Row offsets: a shift when the row pitch is a power of two (packed X at N = 1, 2: the 32-bit multiply runs at
+    // a quarter of the rate of other vector instructions), checked once.
+    const unsigned pitch = (unsigned)ldx * 4u;
+    const int pitch_shift = (pitch & (pitch - 1u)) == 0u ? __builtin_ctz(pitch) : -1;
     auto gather = [&](unsigned k, const int (&c)[E], float (&x)[E][V]) {
-        const unsigned long long from = (unsigned long long)js0 + (unsigned long long)k * W;
-        const int left = from < je1 ? (int)((unsigned long long)je1 - from < (unsigned long long)W ? (unsigned long long)je1 - from : (unsigned long long)W) : 0;
-        if (x_small) {
+        if ((unsigned long long)k * W * 4ull >= chunk_bytes && chunk_bytes != 0ull) {
+            // no such block: nothing to request (the loop's last iteration)
 #pragma unroll
             for (int e = 0; e < E; ++e)
-                buffer_load_vec<V>(rx, e * kWave + lane < left ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e], second);
+#pragma unroll
+                for (int i = 0; i < V; ++i) x[e][i] = 0.0f;
+        } else if (x_small) {
+            if (pitch_shift >= 0) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) buffer_load_vec<V>(rx, (unsigned)c[e] << pitch_shift, x[e], second);
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) buffer_load_vec<V>(rx, (unsigned)c[e] * pitch, x[e], second);
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < E; ++e)
-                load_vec_dword_aligned<V>(X + (size_t)(e * kWave + lane < left ? c[e] : 0) * ldx + n0, x[e], second);
+                load_vec_dword_aligned<V>(X + (size_t)c[e] * ldx + n0, x[e], second);
         }
     };
     // end offset of row `first + lane` (rows past the last one read as 0)
