@@ -24,6 +24,8 @@ and writes its per-cell records under RESULTS_DIR):
     --suite widths    the adaptive call at 34 dense widths from 1 to 128 on three matrices
     --suite holdout   the shipped selection rules scored on matrices they were not fitted on
     --suite layouts   the balanced sequential kernel's wide-N column layouts on the GNN configuration
+    --suite gather    dgsp_gather_probe on synthetic index patterns (what a gather costs per lane layout)
+    --suite colranges the GNN configuration as passes over column ranges of A (Y accumulated pass by pass)
 """
 from __future__ import annotations
 
@@ -48,8 +50,15 @@ RESULTS_DIR = "gpurun_out"     # per-cell records of the suites
 # separate runs, scaled by the same counters on dgsp_copy_f32).  These are NOT measured by this run: they are
 # copied from the named summaries under profiles/, taken on the same build, and the JSON line says so
 # ("traffic_source").  A cell without an entry reports null.
+_TRAFFIC_SOURCE = "profiles/selected_kernels_time_traffic_occupancy.md (rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by the copy kernel)"
 MEASURED_TRAFFIC = {
-    # "kernel/workload/N": (bytes, source)
+    # "kernel/workload/N": (bytes fetched + bytes written per launch of the main kernel, source)
+    "nb_pr/rmat_spmv/N1": (169.3e6 + 5.1e6, _TRAFFIC_SOURCE),
+    "nb_sr/rmat_gnn/N128": (5376.8e6 + 644.3e6, _TRAFFIC_SOURCE),
+    "nb_sr/rmat_gnn/N32": (1147.9e6 + 161.1e6, _TRAFFIC_SOURCE),
+    "nb_pr/stencil/N1": (488.6e6 + 9.5e6, _TRAFFIC_SOURCE),
+    "rs_sr/stencil/N8": (617.3e6 + 67.1e6, _TRAFFIC_SOURCE),
+    "rs_pr/uniform64/N4": (271.2e6 + 5.3e6, _TRAFFIC_SOURCE),
 }
 
 
@@ -675,6 +684,91 @@ def run_layouts(args):
     return 0
 
 
+def run_gather(args):
+    """dgsp_gather_probe on synthetic index patterns (55.7 M indices into 2 M floats, the stencil's sizes): what the
+    memory pipeline charges for a gather as a function of how the lanes of a wave fall onto 128-byte lines."""
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_gather.jsonl")
+    n, K = 55742968, 2097152
+    out = torch.empty(dg.dgsp_gather_probe_out_len(), device="cuda:0")
+    x = torch.zeros(K, device="cuda:0")
+    i = torch.arange(n, device="cuda:0", dtype=torch.int64)
+    patterns = {
+        "consecutive (every wave one run of 64)": lambda: i % K,
+        "runs of 16 consecutive at scattered places": lambda: (i // 16) * 977 % (K - 16) + (i % 16),
+        "runs of 4 consecutive at scattered places": lambda: (i // 4) * 977 % (K - 4) + (i % 4),
+        "runs of 3 consecutive at scattered places": lambda: (i // 3) * 977 % (K - 4) + (i % 3),
+        "stride 977 (every lane its own line)": lambda: (i * 977) % K,
+        "all lanes the same element": lambda: torch.zeros_like(i),
+    }
+    A, _, _ = make_workload("stencil", 1)
+    patterns["the 27-point stencil's own column indices"] = lambda: torch.from_numpy(A.colidx).to("cuda:0").to(torch.int64)
+    rows = []
+    with open(path, "w") as fh:
+        for name, make in patterns.items():
+            idx = make().to(torch.int32)
+            ms = time_events(None, lambda k: dg.dgsp_gather_probe(out, x, idx), max(8, min(args.steps, 20)), 3)
+            rec = {"pattern": name, "indices": int(idx.numel()), "us": median(ms) * 1e3}
+            rows.append(rec)
+            fh.write(json.dumps(rec) + "\n")
+            print(f"[gather] {name}: {rec['us']:.1f} us", file=sys.stderr, flush=True)
+            del idx
+    print(json.dumps({"suite": "gather", "cells": len(rows), "file": path}))
+    return 0
+
+
+def run_colranges(args):
+    """What passes over column ranges would do to the GNN-style configuration (R-MAT 2^20, N = 128): A is cut on the
+    host into P matrices that hold the entries of one range of columns each (all M rows, CSR order kept), and
+    Y = A_0 X, then Y += A_p X for the others, through the library's own calls (the scaled form with beta = 1).
+    Every pass then touches 1/P of the rows of X - and reads and writes all of Y again."""
+    import numpy as np
+    import torch
+    from paper_2106_16064_amd import binding as dg
+    from paper_2106_16064_amd import workloads as wl
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    path = os.path.join(RESULTS_DIR, args.out or "bench_colranges.jsonl")
+    n = args.n or 128
+    A, X, label = make_workload(args.workload or "rmat_gnn", n)
+    Xd = torch.from_numpy(X).to("cuda:0")
+    Y = torch.empty((A.M, n), dtype=torch.float32, device="cuda:0")
+    row_of = np.repeat(np.arange(A.M, dtype=np.int64), A.row_lengths())
+    steps = max(6, min(args.steps, 12))
+    with open(path, "w") as fh:
+        for how in ("equal_width", "equal_entries"):
+            for P in (1, 2, 4, 8, 16):
+                if how == "equal_width":
+                    cuts = [A.K * q // P for q in range(P + 1)]
+                else:
+                    srt = np.sort(A.colidx)
+                    cuts = [0] + [int(srt[A.nnz * q // P]) for q in range(1, P)] + [A.K]
+                parts = []
+                for q in range(P):
+                    keep = (A.colidx >= cuts[q]) & (A.colidx < cuts[q + 1])
+                    counts = np.bincount(row_of[keep], minlength=A.M)
+                    rowptr = np.concatenate(([0], np.cumsum(counts))).astype(np.int32)
+                    parts.append(dg.DeviceCsr(wl.CsrMatrix(A.M, A.K, rowptr, A.colidx[keep], A.vals[keep], f"{label} cols {q}/{P}")))
+
+                def call(_):
+                    for q, m in enumerate(parts):
+                        if q == 0:
+                            m.spmm(Xd, algo=dg.AUTO, Y=Y)
+                        else:
+                            dg.dgsp_spmm_csr_axpby(m.M, m.K, n, m.nnz, m.rowptr, m.colidx, m.vals, Xd, Y, 1.0, 1.0, dg.AUTO, m.features)
+                ms = time_events(None, call, steps, 2)
+                rec = {"workload": label, "N": n, "cut": how, "passes": P, "entries_per_pass": [int(m.nnz) for m in parts],
+                       "kernels": [dg.dgsp_algo_name(dg.dgsp_select_algo(m.features, n)) for m in parts], "us": median(ms) * 1e3}
+                fh.write(json.dumps(rec) + "\n")
+                fh.flush()
+                print(f"[colranges] {how} P={P}: {rec['us']:.0f} us", file=sys.stderr, flush=True)
+                del parts
+                torch.cuda.empty_cache()
+    print(json.dumps({"suite": "colranges", "file": path}))
+    return 0
+
+
 RMAT_GRID_SKEWS = {"powerlaw": (0.57, 0.19, 0.19, 0.05), "mild": (0.45, 0.15, 0.15, 0.25), "uniform": (0.25, 0.25, 0.25, 0.25)}
 
 
@@ -880,7 +974,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths", "holdout", "layouts"])
+    ap.add_argument("--suite", default="headline", choices=["headline", "configs", "sweep", "size", "ablation", "tiny", "kernel", "fit", "widths", "holdout", "layouts", "gather", "colranges"])
     ap.add_argument("--workload", default=None)
     ap.add_argument("--n", type=int, default=None)
     ap.add_argument("--algo", default="auto")
@@ -906,7 +1000,7 @@ def main():
     dg.lib()
     return {"headline": run_headline, "configs": run_configs, "sweep": run_sweep, "size": run_size,
             "ablation": run_ablation, "tiny": run_tiny, "kernel": run_kernel, "widths": run_widths,
-            "holdout": run_holdout, "layouts": run_layouts}[args.suite](args)
+            "holdout": run_holdout, "layouts": run_layouts, "gather": run_gather, "colranges": run_colranges}[args.suite](args)
 
 
 if __name__ == "__main__":

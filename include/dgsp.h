@@ -447,7 +447,8 @@ int64_t dgsp_gather_probe_out_len(void);
  *   DGSP_PROBE_GATHER             N = 1: dgsp_gather_probe (stream colidx, gather x[colidx], nothing else)
  *   DGSP_PROBE_STREAM_GATHER_FMA  N in {1, 2, 4}: stream colidx and vals in blocks of 512 entries, gather N
  *                                 values of X per entry with one vector load, multiply-add; the load pipeline of
- *                                 the parallel-reduction kernels (next block requested behind this block's gathers)
+ *                                 the balanced parallel kernel (while a block is multiplied the next block's
+ *                                 gathers and the entries of the block after are in flight)
  *   DGSP_PROBE_ROW_GATHER         N a multiple of 4: entries staged in LDS 512 at a time, lane groups walk them
  *                                 and load 16 bytes of the entry's row of X per lane (64 columns per group at most,
  *                                 further columns as further blocks): the walk of the sequential-reduction

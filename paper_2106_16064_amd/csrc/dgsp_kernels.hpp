@@ -1694,11 +1694,11 @@ __global__ __launch_bounds__(kBlock) void gather_probe_kernel(float* __restrict_
 
 // Floor of the parallel-reduction kernels: what they do to memory and nothing else.  A wave takes blocks of
 // 512 consecutive entries; lane l loads entries 64 e + l (coalesced, non-temporal), gathers V dense values for
-// each with one vector load and multiplies-adds them into V private sums.  Three register sets rotate: while
-// block b is multiplied, the gathers of block b + 1 and the entries of block b + 2 are in flight, and the
-// entries of block b + 3 are requested as soon as block b's registers are free.  No row bounds, no reduction
-// across lanes, no result rows: the per-lane sums go to out[thread * V + i] so that the loads stay alive (and so
-// that a test can check their total).
+// each with one vector load and multiplies-adds them into V private sums.  The pipeline is the entry-block
+// kernel's: while block b is multiplied, the gathers of block b + 1 and the entries of block b + 2 are in
+// flight; arriving entries wait in a second register set and are moved over once block b is done.  No row
+// bounds, no reduction across lanes, no result rows: the per-lane sums go to out[thread * V + i] so that the
+// loads stay alive (and so that a test can check their total).
 template <int V>
 __global__ __launch_bounds__(kBlock) void stream_gather_fma_probe_kernel(float* __restrict__ out, const float* __restrict__ X,
                                                                          long long K, int ldx, const int* __restrict__ colidx,
@@ -1716,9 +1716,10 @@ __global__ __launch_bounds__(kBlock) void stream_gather_fma_probe_kernel(float* 
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-    struct Set { int c[E]; float a[E]; float x[E][V]; };
-    // entries of block b (nothing past my share or past the arrays' end: zeros, which add nothing)
-    auto load_entries = [&](long long b, Set& s) {
+    int c[E], lc[E];
+    float a[E], la[E], x[E][V];
+    // entries of block b into the arriving set (nothing past my share or past the arrays' end: zeros, which add nothing)
+    auto load_entries = [&](long long b) {
         const long long from = b * W;
         const unsigned long long bytes = (b < b1 && from < nnz) ? (unsigned long long)(nnz - from) * 4ull : 0ull;
         const __amdgpu_buffer_rsrc_t rc = make_buffer(colidx + (bytes ? from : 0), bytes);
@@ -1726,40 +1727,39 @@ __global__ __launch_bounds__(kBlock) void stream_gather_fma_probe_kernel(float* 
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const unsigned off = (unsigned)(e * kWave + lane) * 4u;
-            s.c[e] = buffer_stream_i32(rc, off);
-            s.a[e] = buffer_stream_f32(ra, off);
+            lc[e] = buffer_stream_i32(rc, off);
+            la[e] = buffer_stream_f32(ra, off);
         }
     };
-    auto gather = [&](long long b, Set& s) {
+    auto take_entries = [&]() {
+#pragma unroll
+        for (int e = 0; e < E; ++e) { c[e] = lc[e]; a[e] = la[e]; }
+    };
+    // dense values for the entries in c (those of block b)
+    auto gather = [&](long long b) {
         const long long left = b < b1 ? nnz - b * W : 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const bool ok = e * kWave + lane < left;
             if (x_small) {
-                buffer_load_vec<V>(rx, ok ? (unsigned)s.c[e] * (unsigned)ldx * 4u : kOutOfRange, s.x[e]);
+                buffer_load_vec<V>(rx, ok ? (unsigned)c[e] * (unsigned)ldx * 4u : kOutOfRange, x[e]);
             } else {
-                load_vec_dword_aligned<V>(X + (size_t)(ok ? s.c[e] : 0) * ldx, s.x[e]);
+                load_vec_dword_aligned<V>(X + (size_t)(ok ? c[e] : 0) * ldx, x[e]);
             }
         }
     };
-    // one step: s0 holds block b (gathers in flight), s1 block b + 1 (entries arrived), s2 block b + 2 (in flight)
-    auto step = [&](long long b, Set& s0, Set& s1) {
-        gather(b + 1, s1);
+    load_entries(b0);
+    take_entries();
+    load_entries(b0 + 1);
+    gather(b0);
+    for (long long b = b0; b < b1; ++b) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
 #pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] = fmaf(s0.a[e], s0.x[e][i], acc[i]);
-        load_entries(b + 3, s0);
-    };
-    Set s0, s1, s2;
-    load_entries(b0, s0);
-    load_entries(b0 + 1, s1);
-    load_entries(b0 + 2, s2);
-    gather(b0, s0);
-    for (long long b = b0; b < b1; b += 3) {
-        step(b, s0, s1);
-        if (b + 1 < b1) step(b + 1, s1, s2);
-        if (b + 2 < b1) step(b + 2, s2, s0);
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(a[e], x[e][i], acc[i]);
+        take_entries();
+        load_entries(b + 2);
+        gather(b + 1);
     }
     const long long t = (long long)blockIdx.x * kBlock + threadIdx.x;
 #pragma unroll
