@@ -407,8 +407,8 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                matrix against a smaller slice of X per pass.
  *   DGSP_ABL_BLOCKS_OFF_XCDS     the balanced sequential kernel with its column blocks as a second grid
  *                                dimension, any XCD taking any block.  DGSP_NB_SR itself, when N >= 128 makes
- *                                2, 4 or 8 column blocks, lets every XCD work on one block only, so that an L2
- *                                sees one block's slice of X.  Both switches are comparisons for the layout
+ *                                2 or 4 column blocks, lets every XCD work on one block only, so that an L2
+ *                                sees one block's slice of X (with 8 blocks that measured slower).  Both switches are comparisons for the layout
  *                                of the wide-N path (Section 2.1.3's kernel at N >= 64) and only go with
  *                                DGSP_NB_SR, else DGSP_ERR_UNSUPPORTED.
  * Unknown bits -> DGSP_ERR_INVALID_ARG.  algo must be one of the four kernels.

@@ -413,7 +413,9 @@ int launch_nb_sr_v(const Problem& p) {
     // A matrix with fewer tiles than the machine has room for waves (two per SIMD) leaves CUs idle: a wave takes a
     // whole tile of 512 items whatever N is.  Narrower column blocks make more workgroups out of the same tiles
     // (65 536 rows of 4 entries at N = 32: 640 tiles on 1024 SIMDs; two blocks of 16 columns instead of one of 32).
-    if (p.nnz >= 0) {
+    // Only where entries make up most of the items: every block walks the row ends again, and in a matrix of
+    // mostly empty rows that walk is the work (262 144 rows with 52 000 entries at N = 32: 33 -> 56 us when split).
+    if (p.nnz >= p.M) {
         const long long tiles = (p.nnz + (long long)p.M + kNbSrTile - 1) / kNbSrTile;
         const long long room = (long long)device_info().cus * kWavesPerBlock * 2;
         while (tiles * cols.blocks < room && cols.logG > 0 && cols.cols_per_block % (2 * V) == 0) {
@@ -428,12 +430,16 @@ int launch_nb_sr_v(const Problem& p) {
     // a tile's rows are stored through 32-bit byte offsets from the tile's first row
     if (p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
     dim3 grid(balanced_blocks(p, kNbSrTile, resident_blocks_per_cu(nb_sr_kernel<V, XBUF, DEPTH, false, RAGGED>), false, col_blocks), col_blocks);
-    // Two, four or eight column blocks of a wide X (N >= 128): every XCD works on one block only, so that an L2 sees
-    // one block's slice of X and the slices do not compete (R-MAT 2^20 at N = 128: 1125 -> 1062 us; uniform columns:
-    // 1190 -> 1188 us).  The grid is then one-dimensional with whole workgroups per XCD.  DGSP_ABL_BLOCKS_OFF_XCDS
-    // keeps the blocks as a second grid dimension (the comparison).
+    // Two or four column blocks of a wide X (N = 128 ... 256): every XCD works on one block only, so that an L2 sees
+    // one block's slice of X and the slices do not compete (R-MAT 2^20 at N = 128: 1125 -> 1062 us, N = 256: 2154 ->
+    // 2097 us; uniform columns: 0 ... +4 %).  With eight blocks (N = 512) every XCD would walk the whole matrix alone,
+    // which measured 10-20 % slower on every matrix tried: from there on the blocks stay a second grid dimension.
+    // The grid is then one-dimensional with whole workgroups per XCD.  DGSP_ABL_BLOCKS_OFF_XCDS keeps the blocks as
+    // a second grid dimension (the comparison); eight blocks of 32 columns (DGSP_ABL_COLUMN_BLOCKS_32 at N = 256)
+    // are tied to XCDs too, so that both comparisons can be combined.
     unsigned pinned = 0;
-    if (!(p.switches & DGSP_ABL_BLOCKS_OFF_XCDS) && p.N >= 128 && (col_blocks == 2 || col_blocks == 4 || col_blocks == 8)) {
+    if (!(p.switches & DGSP_ABL_BLOCKS_OFF_XCDS) && p.N >= 128 &&
+        (col_blocks == 2 || col_blocks == 4 || (col_blocks == 8 && (p.switches & DGSP_ABL_COLUMN_BLOCKS_32)))) {
         pinned = col_blocks;
         const unsigned per_xcd = (grid.x * col_blocks + kXcd - 1) / kXcd;         // as many workgroups as before, in one dimension
         grid = dim3(per_xcd * kXcd, 1);

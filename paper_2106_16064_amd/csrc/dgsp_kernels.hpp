@@ -1270,7 +1270,7 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
     const int logU = kNbSrLogTile - 6 + logG;
     const unsigned U = 1u << logU;
     // Column block and place in the chunk list.  Normally blockIdx.y is the column block and blockIdx.x (made
-    // XCD-contiguous) the place.  pinned_blocks = nb > 0 (a comparison, nb in {2, 4, 8}, gridDim = (8 k, 1)): the
+    // XCD-contiguous) the place.  pinned_blocks = nb > 0 (nb in {2, 4}, or 8 for a comparison; gridDim = (8 k, 1)): the
     // workgroups of XCD x all take column block x % nb, so that an L2 only ever sees one block's slice of X; the
     // 8 / nb XCDs of a block share its chunk list, each a contiguous part.
     unsigned col_block = blockIdx.y;
