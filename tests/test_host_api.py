@@ -222,3 +222,36 @@ def test_default_thresholds_and_their_effect_on_benchmark_shapes():
     small = wl.stencil27_csr(24)                        # 13 824 rows: short of rows for one lane per row
     f = dg.dgsp_features_from_csr_host(small.M, small.K, small.rowptr, small.colidx)
     assert [dg.dgsp_select_algo(f, n) for n in (1, 4, 8)] == [dg.RS_PR, dg.RS_PR, dg.RS_SR]
+
+
+def test_the_benchmark_mirror_of_the_rules_agrees_with_the_library():
+    """bench.py scores recorded timings with a Python copy of the selection rules (`rules_choose`, used by
+    `--suite fit`); the losses it reports are only worth something if that copy picks what `dgsp_select_algo`
+    picks.  Seeded random row statistics around every threshold, every N of the sweeps."""
+    import sys
+    from pathlib import Path
+    sys.path.insert(0, str(Path(__file__).resolve().parents[1]))
+    import bench
+    t = dg.dgsp_get_thresholds()
+    td = {name: getattr(t, name) for name in bench.THRESHOLD_NAMES}
+    rng = np.random.default_rng(7)
+    names = {dg.RS_SR: "rs_sr", dg.RS_PR: "rs_pr", dg.NB_SR: "nb_sr", dg.NB_PR: "nb_pr"}
+    checked = 0
+    for _ in range(4000):
+        M = int(2 ** rng.uniform(8, 22))
+        K = int(2 ** rng.uniform(8, 22))
+        avg = float(rng.choice([0.2, 3.9, 4.0, 16.0, 19.9, 20.1, 27.0, 47.9, 48.1, 64.0, 100.0]) * rng.uniform(0.9, 1.1))
+        cv = float(rng.choice([0.0, 0.04, 0.06, 0.19, 0.21, 0.29, 0.31, 0.59, 0.61, 1.3, 9.0]))
+        nnz = max(1, int(M * avg))
+        f = dg.Features()
+        f.M, f.K, f.nnz = M, K, nnz
+        f.avg_row, f.cv_row, f.stdv_row = nnz / M, cv, cv * (nnz / M)
+        f.max_row = int(rng.choice([4, 27, 63, 64, 65, 200, 40000]))
+        f.min_row = 0
+        f.col_span = float(rng.choice([0.0, 0.01, 0.49, 0.51, 1.0]))
+        for N in (1, 2, 3, 4, 5, 8, 9, 16, 31, 32, 64, 100, 128, 256, 512):
+            rec = {"N": N, "M": M, "K": K, "nnz": nnz, "avg_row": f.avg_row, "cv_row": f.cv_row, "max_row": f.max_row,
+                   "col_span": f.col_span}
+            assert bench.rules_choose(rec, td) == names[dg.dgsp_select_algo(f, N)], (rec, td)
+            checked += 1
+    assert checked == 60000
