@@ -320,7 +320,7 @@ constexpr long long kNbPrTilesPerWave = 12;
 constexpr int kNbPrKq = 2;
 
 inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per_cu, bool parallel,
-                                long long col_blocks = 1) {
+                                long long col_blocks = 1, long long parallel_per_cu_max = 0) {
     const long long cus = device_info().cus;
     const long long cap = cus * blocks_per_cu;
     // entry count unknown on the host (the 10-argument call): what serves large matrices best
@@ -332,6 +332,7 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
     if (parallel) {
         per_cu = tiles / (waves * kNbPrTilesPerWave);
         if (per_cu < 2) per_cu = tiles >= waves * kNbPrTilesPerWave ? 2 : 1;
+        if (parallel_per_cu_max > 0 && per_cu > parallel_per_cu_max) per_cu = parallel_per_cu_max;
     } else {
         // the column blocks of a wide X (grid.y) are resident side by side: count them in
         const long long want = (tiles * col_blocks + waves - 1) / waves;
@@ -345,7 +346,7 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
 // Which pipeline the balanced parallel kernel runs.  Blocks of entries with the next block's gathers in flight
 // during the row logic (nb_pr_kernel) for one or two dense columns per lane on matrices of six million entries
 // and more: 2-6 % faster there on R-MAT matrices of every skew (2^20 vertices, degree 16, power law: 104 -> 98 us
-// per call, main launch 98 -> 90 us), even on the 27-point stencil.  Smaller matrices give a wave only a few
+// per call, main launch 98 -> 90 us) and on random columns; not on banded matrices (see launch_nb_pr_v).  Smaller matrices give a wave only a few
 // blocks, and the longer kernel's start-up costs more than the overlap returns (5-10 % slower from 0.25 to 4
 // million entries), so they keep the tiles of merge-path items (nb_pr_tiled_kernel), as does a call that does
 // not know its entry count.  From three columns per lane on the registers that hold a block's gathered values
@@ -363,11 +364,19 @@ int launch_nb_pr_v(const Problem& p) {
     // the row store addresses a step's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
     const bool forced_blocks = (p.switches & (DGSP_ABL_ENTRY_BLOCKS | DGSP_ABL_SERIAL_SEGMENT_SCAN)) != 0;
+    // A banded matrix (neighbouring rows share their columns: stencils, bands) at one or two columns per lane: its
+    // gathers hit the L1 and are bound by the rate of the CU's address unit, not by latency, so gathers requested a
+    // block ahead gain nothing, and two workgroups per CU leave each wave more of the L1 than four do (27-point
+    // stencil on 128^3 at N = 1: item tiles on 2 / 3 workgroups per CU 132 / 140 us, entry blocks on 2 / 3 / 4
+    // 155 / 139 / 143 us; N = 2: 137 against 152 us; bands of 27 and 64: 116, 123 against 120, 134 us).
+    const bool banded_narrow = kNbPrStreams<V> && banded(p) && !forced_blocks;
     const bool tiled = !kNbPrStreams<V> || (p.switches & DGSP_ABL_ITEM_TILES) != 0 ||
-                       (!forced_blocks && p.nnz < kNbPrStreamNnzMin);          // unknown entry count (-1): tiles
+                       (!forced_blocks && (p.nnz < kNbPrStreamNnzMin || banded_narrow));   // unknown entry count (-1): tiles
     int resident = resident_blocks_per_cu(nb_pr_tiled_kernel<V, KQ>);
     if constexpr (kNbPrStreams<V>) { if (!tiled) resident = resident_blocks_per_cu(nb_pr_kernel<V, KQ>); }
-    const dim3 grid(balanced_blocks(p, tile, resident, true), col_groups);
+    // (three columns per lane, always on item tiles, gain from the smaller grid as well: 150 -> 142 us; four do not)
+    const bool few_waves = banded_narrow || (V == 3 && banded(p));
+    const dim3 grid(balanced_blocks(p, tile, resident, true, 1, few_waves ? 2 : 0), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
     if (p.phase != DGSP_PHASE_PREPARE) {
