@@ -152,6 +152,7 @@ class Rotation:
 def time_steps(rot, algo, steps, warmup, warm=False):
     """Wall-clock ms per step over `steps` back-to-back launches."""
     import torch
+    spin_up(None, lambda i: rot.step(i, algo, warm))
     for i in range(warmup):
         rot.step(i, algo, warm)
     torch.cuda.synchronize()
@@ -162,10 +163,32 @@ def time_steps(rot, algo, steps, warmup, warm=False):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+SPIN_UP_MS = 40.0
+
+
+def spin_up(fn_before, fn_timed, ms=SPIN_UP_MS):
+    """Untimed launches for `ms` of wall time before a measurement: while the host builds the next matrix the device
+    idles and its clocks fall, and the first few milliseconds of work afterwards run up to 5 % slower (27-point
+    stencil, N = 1: 138 us in the first measurement after a second of idling, 131 us in the next four and after
+    a spin-up)."""
+    import torch
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < ms * 1e-3:
+        if fn_before:
+            fn_before(i)
+        fn_timed(i)
+        i += 1
+        if i % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+
+
 def time_events(fn_before, fn_timed, steps, warmup):
     """Per-launch durations (ms) of fn_timed(i), bracketed by HIP events on the
     launch stream; fn_before(i) runs untimed just before each launch."""
     import torch
+    spin_up(fn_before, fn_timed)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     for i in range(warmup):
         if fn_before:
@@ -187,6 +210,7 @@ def time_event_batches(fn_before, fn_timed, batch, batches, warmup):
     launches (i = 0..batch-1), so the pair's own cost is spread over the batch; fn_before(i) runs
     untimed for every i before the batch starts."""
     import torch
+    spin_up(fn_before, fn_timed)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(batches)]
     for b in range(warmup + batches):
         if fn_before:

@@ -384,12 +384,12 @@ int dgsp_spmm_csr_axpby(int64_t M, int64_t K, int64_t N, int64_t nnz,
  *                                only be requested after the previous tile's row ends are counted.
  *   DGSP_ABL_ENTRY_BLOCKS        the balanced parallel kernel walking blocks of entries instead, whose
  *                                addresses are known ahead, with the next block's gathers in flight during
- *                                the row logic.  DGSP_NB_PR itself takes entry blocks at one or two dense
+ *                                the row logic.  DGSP_NB_PR itself takes entry blocks at up to four dense
  *                                columns per lane from six million entries on unless the features say the matrix
  *                                is banded (col_span <= 0.05), and item tiles otherwise;
  *                                the two switches force one or the other: the comparison for that choice.
- *                                Only DGSP_NB_PR (entry blocks: only at widths that run one or two columns
- *                                per lane, see DGSP_ABL_SERIAL_SEGMENT_SCAN), not both, else
+ *                                Only DGSP_NB_PR (entry blocks: only at widths that run up to four columns
+ *                                per lane, i.e. not where N is a multiple of 8 or N = 5, 6, 7), not both, else
  *                                DGSP_ERR_UNSUPPORTED.
  *   DGSP_ABL_SERIAL_SEGMENT_SCAN the balanced parallel kernel with its segment reduction done as a serial
  *                                scan: the lanes' partial sums go to LDS and one lane adds them up in order,

@@ -344,17 +344,17 @@ inline unsigned balanced_blocks(const Problem& p, long long tile, int blocks_per
 }
 
 // Which pipeline the balanced parallel kernel runs.  Blocks of entries with the next block's gathers in flight
-// during the row logic (nb_pr_kernel) for one or two dense columns per lane on matrices of six million entries
+// during the row logic (nb_pr_kernel) for up to four dense columns per lane on matrices of six million entries
 // and more: 2-6 % faster there on R-MAT matrices of every skew (2^20 vertices, degree 16, power law: 104 -> 98 us
-// per call, main launch 98 -> 90 us) and on random columns; not on banded matrices (see launch_nb_pr_v).  Smaller matrices give a wave only a few
-// blocks, and the longer kernel's start-up costs more than the overlap returns (5-10 % slower from 0.25 to 4
-// million entries), so they keep the tiles of merge-path items (nb_pr_tiled_kernel), as does a call that does
-// not know its entry count.  From three columns per lane on the registers that hold a block's gathered values
-// halve the resident waves (176 VGPRs at V = 4), which costs more than the overlap gives (stencil N = 4:
-// 150 -> 201 us): tiles as well.  DGSP_ABL_ITEM_TILES / DGSP_ABL_ENTRY_BLOCKS force one or the other where both
-// exist (the comparison for this choice).
+// per call at N = 1, main launch 98 -> 90 us; N = 3: 122 -> 116 us, N = 4: 125 -> 120 us) and on random columns; not
+// on banded matrices (see launch_nb_pr_v).  Smaller matrices give a wave only a few blocks, and the longer kernel's
+// start-up costs more than the overlap returns (5-10 % slower from 0.25 to 4 million entries), so they keep the
+// tiles of merge-path items (nb_pr_tiled_kernel), as does a call that does not know its entry count.  With eight
+// columns per lane the registers that hold a block's gathered values cost more occupancy than the overlap gives
+// (R-MAT N = 8: 162 -> 178 us): tiles as well.  DGSP_ABL_ITEM_TILES / DGSP_ABL_ENTRY_BLOCKS force one or the other
+// where both exist (the comparison for this choice).
 template <int V>
-constexpr bool kNbPrStreams = V <= 2;
+constexpr bool kNbPrStreams = V <= 4;
 constexpr long long kNbPrStreamNnzMin = 6000000;
 
 template <int V, int KQ>
@@ -364,18 +364,18 @@ int launch_nb_pr_v(const Problem& p) {
     // the row store addresses a step's rows with 32-bit byte offsets: tile rows * N * 4 must fit
     if (col_groups > 65535u || p.ldy > kBalancedLdyMax) return DGSP_ERR_UNSUPPORTED;
     const bool forced_blocks = (p.switches & (DGSP_ABL_ENTRY_BLOCKS | DGSP_ABL_SERIAL_SEGMENT_SCAN)) != 0;
-    // A banded matrix (neighbouring rows share their columns: stencils, bands) at one or two columns per lane: its
-    // gathers hit the L1 and are bound by the rate of the CU's address unit, not by latency, so gathers requested a
-    // block ahead gain nothing, and two workgroups per CU leave each wave more of the L1 than four do (27-point
-    // stencil on 128^3 at N = 1: item tiles on 2 / 3 workgroups per CU 132 / 140 us, entry blocks on 2 / 3 / 4
-    // 155 / 139 / 143 us; N = 2: 137 against 152 us; bands of 27 and 64: 116, 123 against 120, 134 us).
-    const bool banded_narrow = kNbPrStreams<V> && banded(p) && !forced_blocks;
+    // A banded matrix (neighbouring rows share their columns: stencils, bands): its gathers hit the L1 and are bound
+    // by the rate of the CU's address unit, not by latency, so gathers requested a block ahead gain nothing, and at up
+    // to three columns per lane two workgroups per CU leave each wave more of the L1 than four do (27-point stencil on
+    // 128^3 at N = 1: item tiles on 2 / 3 workgroups per CU 132 / 140 us, entry blocks on 2 / 3 / 4 155 / 139 / 143 us;
+    // N = 2: 137 against 152 us; N = 3: 142 against 150 us; bands of 27 and 64: 116, 123 against 120, 134 us; with
+    // four columns per lane the larger grid is as good: 153 / 148 / 149 us on 2 / 3 / 4).
+    const bool banded_x = banded(p) && !forced_blocks;
     const bool tiled = !kNbPrStreams<V> || (p.switches & DGSP_ABL_ITEM_TILES) != 0 ||
-                       (!forced_blocks && (p.nnz < kNbPrStreamNnzMin || banded_narrow));   // unknown entry count (-1): tiles
+                       (!forced_blocks && (p.nnz < kNbPrStreamNnzMin || banded_x));   // unknown entry count (-1): tiles
     int resident = resident_blocks_per_cu(nb_pr_tiled_kernel<V, KQ>);
     if constexpr (kNbPrStreams<V>) { if (!tiled) resident = resident_blocks_per_cu(nb_pr_kernel<V, KQ>); }
-    // (three columns per lane, always on item tiles, gain from the smaller grid as well: 150 -> 142 us; four do not)
-    const bool few_waves = banded_narrow || (V == 3 && banded(p));
+    const bool few_waves = banded_x && V <= 3;
     const dim3 grid(balanced_blocks(p, tile, resident, true, 1, few_waves ? 2 : 0), col_groups);
     if (p.phase != DGSP_PHASE_MAIN)
         if (int rc = launch_prepare(p, grid.x * kWavesPerBlock * kSubRanges, 6, -1)) return rc;
@@ -387,9 +387,13 @@ int launch_nb_pr_v(const Problem& p) {
             else
                 DGSP_LAUNCH((nb_pr_tiled_kernel<V, KQ>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
         } else if constexpr (kNbPrStreams<V>) {
-            if (p.switches & DGSP_ABL_SERIAL_SEGMENT_SCAN)
-                DGSP_LAUNCH((nb_pr_kernel<V, KQ, false, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
-            else if (p.scaled)
+            if constexpr (V <= 2) {
+                if (p.switches & DGSP_ABL_SERIAL_SEGMENT_SCAN) {
+                    DGSP_LAUNCH((nb_pr_kernel<V, KQ, false, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y);
+                    return DGSP_OK;
+                }
+            }
+            if (p.scaled)
                 DGSP_LAUNCH((nb_pr_kernel<V, KQ, true>), grid, p.M, p.K, p.N, p.ldx, p.ldy, p.rowptr, p.colidx, p.vals, p.X, p.Y,
                             Scaling{p.alpha, p.beta});
             else
@@ -611,13 +615,13 @@ extern "C" int dgsp_spmm_csr_ablation(int64_t M, int64_t K, int64_t N, int64_t n
                      DGSP_ABL_COLUMN_BLOCKS_32 | DGSP_ABL_BLOCKS_OFF_XCDS | DGSP_ABL_ENTRY_BLOCKS))
         return DGSP_ERR_INVALID_ARG;
     if ((switches & DGSP_ABL_ENTRY_BLOCKS) &&
-        (algo != DGSP_NB_PR || (switches & DGSP_ABL_ITEM_TILES) || nb_pr_lane_width(N, switches) > 2))
+        (algo != DGSP_NB_PR || (switches & DGSP_ABL_ITEM_TILES) || nb_pr_lane_width(N, switches) > 4))
         return DGSP_ERR_UNSUPPORTED;
     if ((switches & (DGSP_ABL_COLUMN_BLOCKS_32 | DGSP_ABL_BLOCKS_OFF_XCDS)) && algo != DGSP_NB_SR) return DGSP_ERR_UNSUPPORTED;
     if ((switches & DGSP_ABL_NO_SPARSE_STAGING) && algo != DGSP_RS_SR) return DGSP_ERR_UNSUPPORTED;
     if ((switches & DGSP_ABL_ITEM_TILES) && algo != DGSP_NB_PR) return DGSP_ERR_UNSUPPORTED;
     if (switches & DGSP_ABL_SERIAL_SEGMENT_SCAN) {
-        // offered where the balanced parallel kernel runs its entry-block pipeline: one or two dense columns per lane
+        // offered at one or two dense columns per lane (on the entry-block pipeline)
         const bool narrow = nb_pr_lane_width(N, switches) <= 2;
         if (algo != DGSP_NB_PR || (switches & DGSP_ABL_ITEM_TILES) || !narrow) return DGSP_ERR_UNSUPPORTED;
     }

@@ -58,6 +58,31 @@ def test_power_law_spmv(dg, rmat20):
     run_cell(dg, rmat20, wl.dense_matrix(rmat20.K, 1, "uniform", seed=0), (-1, 3, 2, 1, 0))
 
 
+@pytest.mark.parametrize("N", [2, 3, 4])
+def test_power_law_narrow_spmm_plain_and_scaled(dg, rmat20, N):
+    """The power-law matrix at two to four dense columns: sixteen million entries, so the balanced parallel kernel
+    walks entry blocks at two, three and four columns per lane - in its plain form and in the scaled one
+    (alpha A X + beta Y), which are separate instantiations."""
+    import torch
+    A = rmat20
+    X = wl.dense_matrix(A.K, N, "uniform", seed=N)
+    run_cell(dg, A, X, (3, -1))
+    yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
+    Y0 = np.random.default_rng(N).uniform(-1.0, 1.0, size=(A.M, N)).astype(np.float32)
+    alpha, beta = -2.0, 0.5
+    want = alpha * yref + beta * Y0.astype(np.float64)
+    bound = abs(alpha) * bnd + abs(beta) * np.abs(Y0.astype(np.float64))
+    dA = dg.DeviceCsr(A)
+    dX = torch.from_numpy(X).cuda()
+    for algo in (3, -1):
+        print(f"[case] {A.name} N={N} scaled algo={NAMES[algo]}", flush=True)
+        dY = torch.from_numpy(Y0).cuda()
+        dg.dgsp_spmm_csr_axpby(A.M, A.K, N, A.nnz, dA.rowptr, dA.colidx, dA.vals, dX, dY, alpha, beta, algo, dA.features)
+        torch.cuda.synchronize()
+        ok, worst = oracle.within_bound(dY.cpu().numpy(), want, bound, TOL)
+        assert ok, f"scaled {NAMES[algo]} N={N}: worst |err|/bound {worst:.3e}"
+
+
 @pytest.mark.parametrize("N", [32, 64, 128])
 def test_gnn_spmm(dg, rmat20, N):
     A = wl.CsrMatrix(rmat20.M, rmat20.K, rmat20.rowptr, rmat20.colidx,

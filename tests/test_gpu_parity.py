@@ -392,14 +392,15 @@ def test_switched_off_optimisations_compute_the_same_product(dg, N):
         assert ok, f"{ALGO_NAMES[algo]} switches={sw} N={N}: worst |err|/bound = {worst:.3e}"
 
 
-@pytest.mark.parametrize("N", [1, 2])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 9, 12])
 @pytest.mark.parametrize("kind", ["rmat", "mostly_empty", "hub", "stencil"])
 def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
-    """At one or two dense columns per lane DGSP_NB_PR walks blocks of entries (gathers requested a block ahead);
-    the ablation switch brings back the tiles of merge-path items.  Both against the oracle, on structures that
-    stress what differs: long stretches of empty rows (several steps per block), rows spanning many blocks, and
-    short regular rows.  The third variant replaces the DPP segment reduction by a serial scan (the comparison
-    kernel of Section 2.1.1)."""
+    """At up to four dense columns per lane DGSP_NB_PR can walk blocks of entries (gathers requested a block ahead)
+    or tiles of merge-path items; the ablation switches force one or the other at any size.  Both against the
+    oracle, on structures that stress what differs: long stretches of empty rows (several steps per block), rows
+    spanning many blocks, and short regular rows; N = 9 and 12 run several passes of three and four columns.  The
+    third variant (one or two columns per lane only) replaces the DPP segment reduction by a serial scan (the
+    comparison kernel of Section 2.1.1)."""
     if kind == "rmat":
         A = wl.rmat_csr(scale=15, avg_degree=16, seed=31)
     elif kind == "mostly_empty":
@@ -412,7 +413,7 @@ def test_both_pipelines_of_the_balanced_parallel_kernel(dg, kind, N):
         A = wl.stencil27_csr(24, seed=34)
     X = wl.dense_matrix(A.K, N, "uniform", seed=35 + N)
     yref, bnd = oracle.spmm_ref(A.M, A.K, N, A.rowptr, A.colidx, A.vals, X)
-    for sw in (0, dg.ABL_ITEM_TILES, dg.ABL_ENTRY_BLOCKS, dg.ABL_SERIAL_SEGMENT_SCAN):
+    for sw in (0, dg.ABL_ITEM_TILES, dg.ABL_ENTRY_BLOCKS) + ((dg.ABL_SERIAL_SEGMENT_SCAN,) if N <= 2 else ()):
         print(f"[case] nb_pr pipelines {kind} N={N} switches={sw}", flush=True)
         Y = _ablation_run(dg, A, X, dg.NB_PR, sw)
         assert not np.isnan(Y).any()
@@ -446,7 +447,8 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     Y = torch.zeros((A.M, 2), device="cuda:0")
     L = dg.lib()
     args = (A.M, A.K, 2, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
-    # the same with N = 4 (refused before anything is launched, so the narrower X and Y do not matter)
+    # the same with N = 8 and N = 4 (refused before anything is launched, so the narrower X and Y do not matter)
+    args8 = (A.M, A.K, 8, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
     args4 = (A.M, A.K, 4, A.nnz, dA.rowptr.data_ptr(), dA.colidx.data_ptr(), dA.vals.data_ptr(), X.data_ptr(), Y.data_ptr())
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_NO_SPARSE_STAGING, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, 1 << 12, None, None) == dg.ERR_INVALID_ARG
@@ -454,7 +456,7 @@ def test_ablation_entry_rejects_what_it_does_not_offer(dg):
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_PR, dg.ABL_SERIAL_SEGMENT_SCAN, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_COLUMN_BLOCKS_32, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_ENTRY_BLOCKS | dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
-    assert L.dgsp_spmm_csr_ablation(*args4, dg.NB_PR, dg.ABL_ENTRY_BLOCKS, None, None) == dg.ERR_UNSUPPORTED
+    assert L.dgsp_spmm_csr_ablation(*args8, dg.NB_PR, dg.ABL_ENTRY_BLOCKS, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_SR, dg.ABL_ENTRY_BLOCKS, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.RS_SR, dg.ABL_BLOCKS_OFF_XCDS, None, None) == dg.ERR_UNSUPPORTED
     assert L.dgsp_spmm_csr_ablation(*args, dg.NB_PR, dg.ABL_SERIAL_SEGMENT_SCAN | dg.ABL_ITEM_TILES, None, None) == dg.ERR_UNSUPPORTED
