@@ -57,8 +57,8 @@ MEASURED_TRAFFIC = {
     "nb_sr/rmat_gnn/N128": (5376.8e6 + 644.3e6, _TRAFFIC_SOURCE),
     "nb_sr/rmat_gnn/N32": (1147.9e6 + 161.1e6, _TRAFFIC_SOURCE),
     "nb_pr/stencil/N1": (505.6e6 + 8.7e6, _TRAFFIC_SOURCE),
-    "rs_sr/stencil/N8": (617.3e6 + 67.1e6, _TRAFFIC_SOURCE),
-    "rs_pr/uniform64/N4": (271.2e6 + 5.3e6, _TRAFFIC_SOURCE),
+    "rs_sr/stencil/N8": (619.6e6 + 67.1e6, _TRAFFIC_SOURCE),
+    "rs_pr/uniform64/N4": (272.7e6 + 5.2e6, _TRAFFIC_SOURCE),
 }
 
 
