@@ -211,7 +211,7 @@ inline bool banded(const Problem& p) { return p.col_span > 0.0 && p.col_span <= 
 // The sequential kernels give a lane four dense columns whenever a row has four: the memory pipeline takes
 // dwordx2 / dwordx4 accesses at any dword address, so neither the alignment of X and Y nor their leading
 // dimensions restrict the width.  When N is not a multiple of four the last lane of a row takes the row's last
-// four columns and leaves out those it shares with its neighbour (RAGGED).
+// four columns; those it shares with its neighbour are the neighbour's to add or to scale (RAGGED).
 struct SrShape { int v; bool ragged; };
 inline SrShape sr_shape(const Problem& p) {
     if (p.switches & DGSP_ABL_SCALAR_DENSE_LOADS) return {1, false};

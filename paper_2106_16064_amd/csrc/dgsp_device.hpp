@@ -274,7 +274,8 @@ __device__ __forceinline__ float buffer_stream_f32(__amdgpu_buffer_rsrc_t r, uns
 // lane `gl` of a group normally owns [first, first + V) with first = block * cols_per_block + gl * V.  RAGGED (N is
 // not a multiple of V, N >= V): the lane whose window would pass N takes the last V columns of the row instead, so
 // that every load stays inside the row; `skip` of them also belong to its left neighbour, which computes the same
-// sums from the same entries in the same order - the lane keeps them out of everything it writes.
+// sums from the same entries in the same order - the lane keeps them out of what it adds to memory and of the
+// scaled form's stores (plain stores may repeat them: the bits are the same).
 struct LaneColumns {
     long long first;    // first column of the window
     int skip;           // leading columns of the window that are the neighbour's (0 < skip < V on one lane at most)
@@ -292,13 +293,17 @@ __device__ __forceinline__ LaneColumns lane_columns(unsigned block, int cols_per
     return c;
 }
 
-// Stores a lane's V results at byte_offset (kOutOfRange: nothing), leaving out its first `skip`.
-// `tail` = N % V (wave-uniform): the lane with skip != 0 owns exactly its last `tail` values, so they leave in
-// one more store of that width, issued by the whole wave and switched off everywhere else.
-template <int V, bool RAGGED, int AUX = 0>
+// Stores a lane's V results at byte_offset (kOutOfRange: nothing).  With RAGGED the last lane of a row shares its
+// first `skip` columns with its neighbour, and both hold the same bits there (the same entries in the same order
+// went into them).  In the plain product both may store them: whichever write lands last changes nothing, also
+// when the neighbour sits in another column block and writes at another time.  LEAVE_SHARED_OUT (the scaled form,
+// where a result depends on the old Y and the neighbour may have replaced that already): the lane with skip != 0
+// stores exactly its last `tail` = N % V values (wave-uniform) in one more store of that width, issued by the
+// whole wave and switched off everywhere else.
+template <int V, bool RAGGED, int AUX = 0, bool LEAVE_SHARED_OUT = true>
 __device__ __forceinline__ void buffer_store_columns(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_offset, const float (&x)[V],
                                                      int skip, int tail) {
-    if constexpr (!RAGGED) {
+    if constexpr (!RAGGED || !LEAVE_SHARED_OUT) {
         buffer_store_vec<V, AUX>(rsrc, byte_offset, x);
     } else {
         static_assert(V == 4, "the shared lane exists at four columns per lane only");

@@ -256,12 +256,14 @@ __global__ __launch_bounds__(kBlock) void rs_sr_kernel(int M, long long K, int N
         if (live && col_ok) {
             float* y = Y + (size_t)row * ldy + n;
             if constexpr (AXPBY) scale_into<V, true>(acc, y, sc);
-            if (RAGGED && mine.skip != 0) {
+            if (AXPBY && RAGGED && mine.skip != 0) {
+                // the scaled result depends on the old Y, which the neighbour (another column block, another time)
+                // may have replaced: the shared columns are the neighbour's to write
 #pragma unroll
                 for (int i = 1; i < V; ++i)
                     if (i >= mine.skip) y[i] = acc[i];
             } else {
-                store_vec_dword_aligned<V>(y, acc);
+                store_vec_dword_aligned<V>(y, acc);      // plain product: shared columns hold the same bits in both lanes
             }
         }
     }
@@ -1380,9 +1382,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                         for (int i = 0; i < V; ++i) out[i] = 0.0f;
                         scale_into<V>(out, yrows, off, sc);               // beta * Y
-                        buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, out, mine.skip, tail);
+                        buffer_store_columns<V, RAGGED, kStoreAux, true>(yrows, off, out, mine.skip, tail);
                     } else {
-                        buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, zero, mine.skip, tail);
+                        buffer_store_columns<V, RAGGED, kStoreAux, false>(yrows, off, zero, mine.skip, tail);
                     }
                 }
             }
@@ -1451,9 +1453,9 @@ __global__ __launch_bounds__(kBlock) void nb_sr_kernel(int M, long long K, int N
 #pragma unroll
                     for (int i = 0; i < V; ++i) out[i] = acc[i];
                     scale_into<V>(out, yrows, off, sc);
-                    buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, out, mine.skip, tail);
+                    buffer_store_columns<V, RAGGED, kStoreAux, true>(yrows, off, out, mine.skip, tail);
                 } else {
-                    buffer_store_columns<V, RAGGED, kStoreAux>(yrows, off, acc, mine.skip, tail);
+                    buffer_store_columns<V, RAGGED, kStoreAux, false>(yrows, off, acc, mine.skip, tail);
                 }
                 if (closing) {
                     if (!direct) to_slot(true);
